@@ -1,0 +1,186 @@
+#!/usr/bin/env python3
+"""Benchmark of the BPDQ per-layer quantization pass on one MI355X.
+
+One "step" = the whole hot path for one layer: zero H, accumulate the calibration Hessian
+over all tokens, damp + factor (U = chol(H^-1)), and the group/column sweep with lazy block
+updates.  Inputs (W and all activation chunks) are resident in HBM before the timed region.
+Prints ONE JSON line (metric = Mparams quantized/s).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_MFMA_F32_TFLOPS = 157.3    # MI355X dense fp32 matrix peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="cfg2_qwen7b_attn")
+    ap.add_argument("--tokens-per-call", type=int, default=0,
+                    help="tokens per bpdq_hessian_accumulate call (0 = all tokens in one call)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--phases-only", default="", help="comma list of hessian,prepare,quantize (profiling)")
+    return ap.parse_args()
+
+
+def cpu_baseline(wl, W_cpu, scales_cpu, n_tok_sub=8192, rows_sub=128):
+    """The oracle, as it stands, on a bounded sample of the same workload; its time is scaled
+    linearly to the full layer (tokens for the Hessian, rows for the sweep)."""
+    import numpy as np
+    import torch
+    from threadpoolctl import threadpool_info
+    from oracle import bpdq_oracle as orc
+    from paper_2602_04163_amd import workloads as wk
+
+    sub = wl.scaled(n_tok=n_tok_sub, chunk=min(wl.chunk, n_tok_sub))
+    H = np.zeros((wl.d_in, wl.d_in))
+    # time only the oracle's own work: the chunks are generated beforehand
+    chunks = [wk.make_activation_chunk(sub, c, scales_cpu).numpy() for c in range(wk.n_chunks(sub))]
+    t0 = time.perf_counter()
+    for Xc in chunks:
+        orc.hessian_accumulate(Xc, H)
+    t_h = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    U, dead, info = orc.prepare(H, wl.damp)
+    t_p = time.perf_counter() - t0
+    rows = min(rows_sub, wl.d_out)
+    t0 = time.perf_counter()
+    orc.quantize_layer(W_cpu[:rows].numpy(), U, dead, wl.bits, wl.group, wl.block,
+                       wl.refine_iters, alpha=wl.alpha)
+    t_q = time.perf_counter() - t0
+    t_full = t_h * (wl.n_tok / n_tok_sub) + t_p + t_q * (wl.d_out / rows)
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [torch.get_num_threads()])
+    return {
+        "value": wl.params / t_full / 1e6, "unit": "Mparams/s", "cores": int(threads),
+        "kind": "oracle",
+        "sample": (f"numpy fp64 oracle: Hessian on {n_tok_sub} of {wl.n_tok} tokens ({t_h:.2f} s, "
+                   f"scaled x{wl.n_tok / n_tok_sub:.0f}), prepare at full size ({t_p:.2f} s), sweep on "
+                   f"{rows} of {wl.d_out} rows ({t_q:.2f} s, scaled x{wl.d_out / rows:.0f}); "
+                   f"extrapolated full layer {t_full:.1f} s"),
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives are part of it); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2602_04163_amd import binding as bq
+    from paper_2602_04163_amd import workloads as wk
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    bq.load()
+    dev = torch.device("cuda:0")
+    wl = wk.WORKLOADS[args.workload]
+    d_out, d_in, n_tok = wl.d_out, wl.d_in, wl.n_tok
+
+    # ---- inputs, resident in HBM --------------------------------------------------------
+    W = wk.make_weight(wl, device=dev)
+    scales = wk.channel_scales(wl, device=dev)
+    X = torch.empty((n_tok, d_in), device=dev, dtype=torch.float32)
+    for c in range(wk.n_chunks(wl)):
+        wk.make_activation_chunk(wl, c, scales, device=dev, out=X[c * wl.chunk:(c + 1) * wl.chunk])
+    per_call = args.tokens_per_call if args.tokens_per_call > 0 else n_tok
+    calls = [(a, min(a + per_call, n_tok)) for a in range(0, n_tok, per_call)]
+
+    # ---- outputs and workspaces, allocated once -----------------------------------------
+    H = torch.zeros((d_in, d_in), device=dev)
+    U = torch.empty((d_in, d_in), device=dev)
+    p = bq.make_params(wl.bits, wl.group, wl.block, wl.refine_iters, wl.alpha)
+    ws_h = torch.empty(max(256, max(bq.bpdq_hessian_workspace_bytes(b - a, d_in) for a, b in calls)),
+                       dtype=torch.uint8, device=dev)
+    ws_p = torch.empty(bq.bpdq_prepare_workspace_bytes(d_in), dtype=torch.uint8, device=dev)
+    ws_q = torch.empty(bq.bpdq_quantize_workspace_bytes(d_out, d_in, p), dtype=torch.uint8, device=dev)
+    out = None
+    phases = [s for s in args.phases_only.split(",") if s] or ["hessian", "prepare", "quantize"]
+    ev = {k: [] for k in ("hessian", "prepare", "quantize")}
+
+    def step(record):
+        nonlocal out
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(4)] if record else None
+        if record:
+            marks[0].record()
+        if "hessian" in phases:
+            H.zero_()
+            for a, b in calls:
+                bq.bpdq_hessian_accumulate(X[a:b], H, scale=2.0, symmetrize=False, ws=ws_h)
+        if record:
+            marks[1].record()
+        dead = None
+        if "prepare" in phases:
+            _, dead, _ = bq.bpdq_prepare(H, wl.damp, U=U, ws=ws_p)
+        if record:
+            marks[2].record()
+        if "quantize" in phases:
+            out = bq.bpdq_quantize_layer(W, U, dead, p, want_w_hat=True, ws=ws_q, out=out)
+        if record:
+            marks[3].record()
+            ev["hessian"].append((marks[0], marks[1]))
+            ev["prepare"].append((marks[1], marks[2]))
+            ev["quantize"].append((marks[2], marks[3]))
+
+    if "prepare" not in phases or "hessian" not in phases:
+        # profiling a single phase still needs valid inputs for it
+        saved = phases
+        phases = ["hessian", "prepare", "quantize"]
+        step(False)
+        phases = saved
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    phase_ms = {k: sum(a.elapsed_time(b) for a, b in v) / max(len(v), 1) for k, v in ev.items()}
+
+    # ---- roofline of the dominant kernel: the fp32-MFMA Hessian SYRK ---------------------
+    # algorithmic flops: the symmetric half, d(d+1) multiply-adds' worth per token
+    flops_per_launch = float(d_in) * (d_in + 1) * (n_tok / len(calls))
+    launch_ms = phase_ms["hessian"] / len(calls)
+    achieved = flops_per_launch / (launch_ms * 1e-3) / 1e12 if launch_ms > 0 else 0.0
+    traffic = None
+    tp = os.path.join(ROOT, "profiles", f"hess_syrk_{args.workload}_traffic.json")
+    if os.path.exists(tp) and len(calls) == 1:
+        traffic = json.load(open(tp)).get("hbm_bytes_per_launch")
+    res = {
+        "metric": "Mparams quantized/s per layer (full pass: Hessian + prepare + sweep)",
+        "value": wl.params / (ms_per_step * 1e-3) / 1e6,
+        "unit": "Mparams/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "d_out": d_out, "d_in": d_in, "tokens": n_tok,
+                   "bits": wl.bits, "group": wl.group, "block": wl.block,
+                   "refine_iters": wl.refine_iters, "hessian_calls_per_step": len(calls)},
+        "phase_ms": {k: round(v, 4) for k, v in phase_ms.items()},
+        "quantize_only_mparams_per_s": (wl.params / (phase_ms["quantize"] * 1e-3) / 1e6
+                                        if phase_ms["quantize"] > 0 else None),
+        "roofline": {"kernel": "hess_syrk_f32_kernel", "bound": "mfma", "achieved": achieved,
+                     "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_MFMA_F32_TFLOPS, "traffic": traffic},
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(wl, W.cpu(), scales.cpu())
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

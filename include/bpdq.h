@@ -1,0 +1,114 @@
+/*
+ * bpdq.h -- C ABI of the BPDQ per-layer quantization pass for AMD MI355X (gfx950).
+ *
+ * BPDQ (Bit-Plane Decomposition Quantization on a variable grid) represents a linear
+ * layer's weight as   What = REP(C_0) + sum_{i=1..k} REP(C_i) (.) B_i   (paper Eq. 1):
+ * k binary planes B_i and k+1 real coefficients per (row, group of g input channels),
+ * chosen to minimise || (W - What) X ||_F^2 = tr((W - What) H (W - What)^T)  (Eq. 2).
+ *
+ * Conventions
+ *  - Every pointer is a DEVICE pointer owned by the caller unless marked "host".
+ *    The library allocates nothing: scratch comes from the caller's workspace `ws`
+ *    (256-byte aligned, at least *_workspace_bytes() long).
+ *  - Every call only enqueues work on `stream` (a hipStream_t passed as void*; NULL is
+ *    the default stream) and returns without synchronising.  Calls on one stream are
+ *    ordered; a workspace must not be shared by calls that can run concurrently.
+ *  - Matrices are dense row-major fp32 unless stated.
+ *  - Return value: 0 = enqueued; -n = argument number n (1-based) is invalid;
+ *    BPDQ_ERR_LAUNCH = a HIP call failed.  Numerical failure of bpdq_prepare is reported
+ *    through its device-side `info`, LAPACK style.
+ *  - Results are deterministic: no floating-point atomics anywhere.
+ */
+#ifndef BPDQ_H
+#define BPDQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BPDQ_ERR_LAUNCH (-100)
+
+/* Knobs of the method (paper Sec. 4.1: k in {2,3,4}, g in {64,128,256}, 10 iterations,
+ * alpha = 1e-4). */
+typedef struct bpdq_params {
+  int   bits;           /* k, number of bit-planes: 1..4                                      */
+  int   group;          /* g: 32, 64 or 128; must divide d_in                                 */
+  int   block;          /* lazy-update block B; the effective block is max(B, g); g | B       */
+  int   refine_iters;   /* T >= 0 iterations of (bit-plane update, refit, delta correction);
+                           0 keeps the initialisation + one fit (Sec. 3.2)                    */
+  float alpha;          /* relative ridge of the coefficient fit (Sec. 3.2, end): the
+                           (k+1)x(k+1) normal matrix G gets alpha*tr(G)/(k+1) on its diagonal */
+  int   select_per_row; /* 0: keep the iterate with the smallest group-wise ||E||_F^2 over all
+                           rows (Sec. 3.3).  Other values are rejected.                       */
+} bpdq_params;
+
+/* Library version (major*10000 + minor*100 + patch). */
+int bpdq_version(void);
+
+/* ---- step 1: calibration Hessian (Sec. 3.1, text under Eq. 2: H = X X^T) ---------------
+ * H += scale * Xc^T Xc for one chunk of tokens.
+ *   Xc : n_tok x d_in, one token per row, row stride ldx floats (>= d_in).  This is the
+ *        paper's X (d_in x N, one token per column) in column-major storage.
+ *   H  : d_in x d_in.  Only the upper triangle (j >= i) is accumulated; pass
+ *        symmetrize != 0 (e.g. on the last chunk) to mirror it into the lower triangle.
+ *   scale : 2 reproduces the customary H = 2 X X^T; any positive factor gives the same
+ *        planes and coefficients.
+ *   ws : split-K partial sums; bpdq_hessian_workspace_bytes(n_tok, d_in) bytes (may be 0).
+ * Requirements: d_in % 4 == 0, ldx % 4 == 0, Xc and H 16-byte aligned, n_tok >= 0. */
+size_t bpdq_hessian_workspace_bytes(int n_tok, int d_in);
+int bpdq_hessian_accumulate(const float* Xc, int n_tok, int d_in, int ldx, float scale,
+                            float* H, int symmetrize, void* ws, size_t ws_bytes, void* stream);
+
+/* ---- step 2: damping and U = chol(H^-1) (Sec. 3.1, "Quantization Error Compensation") ---
+ * Reads the upper triangle of H.  Channels with H_ii == 0 are marked dead[i] = 1 and get
+ * H_ii = 1.  Then lambda = damp * mean_i(H_ii), Ht = H + lambda I, and U is the upper
+ * triangular matrix with positive diagonal such that Ht^-1 = U^T U.
+ *   U    : d_in x d_in fp32, full matrix written (strictly lower part = 0); may alias H.
+ *   dead : d_in bytes.
+ *   info : one device int: 0, or the 1-based index of a column whose pivot was not
+ *          positive (Ht not positive definite; U is then undefined).
+ * The factorisation runs in fp64 inside ws. */
+size_t bpdq_prepare_workspace_bytes(int d_in);
+int bpdq_prepare(const float* H, int d_in, float damp, float* U, unsigned char* dead,
+                 int* info, void* ws, size_t ws_bytes, void* stream);
+
+/* ---- steps 3-4: the group/column sweep with lazy block updates (Sec. 3.2, 3.3, App. B.3) -
+ * For every block of max(B, g) columns, left to right, and every group of g columns in it:
+ * 8-bit round-to-nearest initialisation of the planes from the group's current working
+ * weights (Eq. 5), coefficient fit in the metric of the local factor (Eq. 6), then
+ * refine_iters times: column-wise nearest-level bit-plane update with error propagation
+ * (Eq. 3-4, 7-8), coefficient refit, delta correction (Eq. 9); the iterate with the smallest
+ * ||E_group||_F^2 is kept (the initial state counts as iterate 0; ties keep the earliest).
+ * Its propagation error is applied to the rest of the block at once and to all later
+ * columns by one GEMM per block (W'[:, end:] -= E_blk U[blk, end:]).
+ *   W       : d_out x d_in, read only.
+ *   U, dead : from bpdq_prepare (dead may be NULL).
+ *   planes  : uint32 [bits][d_out][d_in/32]; column c of plane B_i (i = 1..bits) is bit
+ *             (c % 32) of word planes[i-1][r][c/32], least significant bit first.
+ *   coefs   : float [bits+1][d_out][d_in/g]; index 0 is the bias C_0.
+ *   W_hat   : float d_out x d_in, or NULL.  Equal to bpdq_dequant(planes, coefs) bit for bit.
+ *   grp_err : double [d_in/g], ||E_group||_F^2 of the kept iterate; their sum is the layer
+ *             objective tr((W-What) Ht (W-What)^T) (App. B.2).
+ *   grp_iter: int [d_in/g], index of the kept iterate (0..refine_iters).
+ * Requirements: d_in % group == 0, d_in % 32 == 0, group | max(block, group). */
+size_t bpdq_quantize_workspace_bytes(int d_out, int d_in, const bpdq_params* p /* host */);
+int bpdq_quantize_layer(const float* W, int d_out, int d_in, const float* U,
+                        const unsigned char* dead, const bpdq_params* p /* host */,
+                        uint32_t* planes, float* coefs, float* W_hat, double* grp_err,
+                        int* grp_iter, void* ws, size_t ws_bytes, void* stream);
+
+/* ---- storage format helpers (Eq. 1) -------------------------------------------------------
+ * codes : uint8 d_out x d_in, bit (i-1) of a code is B_i.  planes as above. */
+int bpdq_pack_planes(const unsigned char* codes, int d_out, int d_in, int bits,
+                     uint32_t* planes, void* stream);
+/* W_hat[r][c] = ((C_0 + b_1 C_1) + b_2 C_2) + ... evaluated in fp32 in this order. */
+int bpdq_dequant(const uint32_t* planes, const float* coefs, int d_out, int d_in, int bits,
+                 int group, float* W_hat, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BPDQ_H */

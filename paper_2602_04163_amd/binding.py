@@ -1,0 +1,197 @@
+"""Thin ctypes binding of libbpdq.so: same names as the C ABI (include/bpdq.h).
+
+Only argument marshalling happens here: torch tensors supply device memory and the
+current HIP stream; every step of the pass runs inside the library's kernels.  There is
+no CPU fallback -- a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbpdq.so")
+_lib = None
+
+EXPORTS = [
+    "bpdq_version",
+    "bpdq_hessian_workspace_bytes", "bpdq_hessian_accumulate",
+    "bpdq_prepare_workspace_bytes", "bpdq_prepare",
+    "bpdq_quantize_workspace_bytes", "bpdq_quantize_layer",
+    "bpdq_pack_planes", "bpdq_dequant",
+]
+
+
+class BpdqParams(ctypes.Structure):
+    _fields_ = [("bits", ctypes.c_int), ("group", ctypes.c_int), ("block", ctypes.c_int),
+                ("refine_iters", ctypes.c_int), ("alpha", ctypes.c_float),
+                ("select_per_row", ctypes.c_int)]
+
+
+class BpdqError(RuntimeError):
+    pass
+
+
+def load():
+    """Load libbpdq.so (built by `python -m paper_2602_04163_amd.build`)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise BpdqError(f"{LIB_PATH} is missing: build it with "
+                        "`python -m paper_2602_04163_amd.build` (there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, ci, cf, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+    pp = ctypes.POINTER(BpdqParams)
+    lib.bpdq_version.restype = ci
+    lib.bpdq_version.argtypes = []
+    lib.bpdq_hessian_workspace_bytes.restype = sz
+    lib.bpdq_hessian_workspace_bytes.argtypes = [ci, ci]
+    lib.bpdq_hessian_accumulate.restype = ci
+    lib.bpdq_hessian_accumulate.argtypes = [vp, ci, ci, ci, cf, vp, ci, vp, sz, vp]
+    lib.bpdq_prepare_workspace_bytes.restype = sz
+    lib.bpdq_prepare_workspace_bytes.argtypes = [ci]
+    lib.bpdq_prepare.restype = ci
+    lib.bpdq_prepare.argtypes = [vp, ci, cf, vp, vp, vp, vp, sz, vp]
+    lib.bpdq_quantize_workspace_bytes.restype = sz
+    lib.bpdq_quantize_workspace_bytes.argtypes = [ci, ci, pp]
+    lib.bpdq_quantize_layer.restype = ci
+    lib.bpdq_quantize_layer.argtypes = [vp, ci, ci, vp, vp, pp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.bpdq_pack_planes.restype = ci
+    lib.bpdq_pack_planes.argtypes = [vp, ci, ci, ci, vp, vp]
+    lib.bpdq_dequant.restype = ci
+    lib.bpdq_dequant.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp]
+    _lib = lib
+    return lib
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _check(rc, name):
+    if rc != 0:
+        raise BpdqError(f"{name} returned {rc}" + (f" (argument {-rc} invalid)" if -99 < rc < 0 else ""))
+
+
+def _dev(t, dtype, name):
+    if not (t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise BpdqError(f"{name}: expected a contiguous {dtype} tensor on the GPU")
+
+
+def _workspace(nbytes, device):
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def bpdq_version() -> int:
+    return load().bpdq_version()
+
+
+def bpdq_hessian_workspace_bytes(n_tok: int, d_in: int) -> int:
+    return load().bpdq_hessian_workspace_bytes(n_tok, d_in)
+
+
+def bpdq_hessian_accumulate(Xc, H, scale=2.0, symmetrize=False, ws=None):
+    """H += scale * Xc^T Xc (upper triangle; mirrored when symmetrize)."""
+    lib = load()
+    _dev(H, torch.float32, "H")
+    if not (Xc.is_cuda and Xc.dtype == torch.float32 and Xc.dim() == 2 and Xc.stride(1) == 1):
+        raise BpdqError("Xc: expected a float32 GPU matrix with unit column stride")
+    n_tok, d_in = Xc.shape
+    if H.shape != (d_in, d_in):
+        raise BpdqError("H: expected d_in x d_in")
+    need = lib.bpdq_hessian_workspace_bytes(n_tok, d_in)
+    if ws is None:
+        ws = _workspace(need, H.device)
+    rc = lib.bpdq_hessian_accumulate(_ptr(Xc), n_tok, d_in, Xc.stride(0) if n_tok > 1 else d_in,
+                                     scale, _ptr(H), int(bool(symmetrize)), _ptr(ws), ws.numel(),
+                                     _stream())
+    _check(rc, "bpdq_hessian_accumulate")
+    return H
+
+
+def bpdq_prepare_workspace_bytes(d_in: int) -> int:
+    return load().bpdq_prepare_workspace_bytes(d_in)
+
+
+def bpdq_prepare(H, damp=0.01, U=None, ws=None):
+    """Returns (U, dead, info): U = chol_upper((H + damp*mean(diag H) I)^-1)."""
+    lib = load()
+    _dev(H, torch.float32, "H")
+    d_in = H.shape[0]
+    if U is None:
+        U = torch.empty_like(H)
+    _dev(U, torch.float32, "U")
+    dead = torch.empty(d_in, dtype=torch.uint8, device=H.device)
+    info = torch.empty(1, dtype=torch.int32, device=H.device)
+    if ws is None:
+        ws = _workspace(lib.bpdq_prepare_workspace_bytes(d_in), H.device)
+    rc = lib.bpdq_prepare(_ptr(H), d_in, damp, _ptr(U), _ptr(dead), _ptr(info), _ptr(ws),
+                          ws.numel(), _stream())
+    _check(rc, "bpdq_prepare")
+    return U, dead, info
+
+
+def make_params(bits, group, block, refine_iters, alpha=1e-4, select_per_row=0) -> BpdqParams:
+    return BpdqParams(bits, group, block, refine_iters, alpha, select_per_row)
+
+
+def bpdq_quantize_workspace_bytes(d_out, d_in, params: BpdqParams) -> int:
+    return load().bpdq_quantize_workspace_bytes(d_out, d_in, ctypes.byref(params))
+
+
+def bpdq_quantize_layer(W, U, dead, params: BpdqParams, want_w_hat=True, ws=None, out=None):
+    """Returns dict(planes, coefs, W_hat, grp_err, grp_iter) of device tensors."""
+    lib = load()
+    _dev(W, torch.float32, "W")
+    _dev(U, torch.float32, "U")
+    d_out, d_in = W.shape
+    k, g = params.bits, params.group
+    dev = W.device
+    if out is None:
+        out = dict(
+            planes=torch.empty((k, d_out, d_in // 32), dtype=torch.int32, device=dev),
+            coefs=torch.empty((k + 1, d_out, d_in // g), dtype=torch.float32, device=dev),
+            W_hat=torch.empty((d_out, d_in), dtype=torch.float32, device=dev) if want_w_hat else None,
+            grp_err=torch.empty(d_in // g, dtype=torch.float64, device=dev),
+            grp_iter=torch.empty(d_in // g, dtype=torch.int32, device=dev),
+        )
+    if ws is None:
+        need = lib.bpdq_quantize_workspace_bytes(d_out, d_in, ctypes.byref(params))
+        if need == 0:
+            raise BpdqError("bpdq_quantize_workspace_bytes: invalid parameters")
+        ws = _workspace(need, dev)
+    rc = lib.bpdq_quantize_layer(_ptr(W), d_out, d_in, _ptr(U), _ptr(dead), ctypes.byref(params),
+                                 _ptr(out["planes"]), _ptr(out["coefs"]), _ptr(out["W_hat"]),
+                                 _ptr(out["grp_err"]), _ptr(out["grp_iter"]), _ptr(ws), ws.numel(),
+                                 _stream())
+    _check(rc, "bpdq_quantize_layer")
+    return out
+
+
+def bpdq_pack_planes(codes, bits):
+    lib = load()
+    _dev(codes, torch.uint8, "codes")
+    d_out, d_in = codes.shape
+    planes = torch.empty((bits, d_out, d_in // 32), dtype=torch.int32, device=codes.device)
+    _check(lib.bpdq_pack_planes(_ptr(codes), d_out, d_in, bits, _ptr(planes), _stream()),
+           "bpdq_pack_planes")
+    return planes
+
+
+def bpdq_dequant(planes, coefs, group):
+    lib = load()
+    _dev(planes, torch.int32, "planes")
+    _dev(coefs, torch.float32, "coefs")
+    bits, d_out, nw = planes.shape
+    d_in = nw * 32
+    W_hat = torch.empty((d_out, d_in), dtype=torch.float32, device=planes.device)
+    _check(lib.bpdq_dequant(_ptr(planes), _ptr(coefs), d_out, d_in, bits, group, _ptr(W_hat),
+                            _stream()), "bpdq_dequant")
+    return W_hat

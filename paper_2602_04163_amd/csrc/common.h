@@ -1,0 +1,36 @@
+// Shared host/device helpers of the BPDQ library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/bpdq.h"
+
+#define BPDQ_HIP_TRY(expr)                      \
+  do {                                          \
+    if ((expr) != hipSuccess) {                 \
+      (void)hipGetLastError();                  \
+      return BPDQ_ERR_LAUNCH;                   \
+    }                                           \
+  } while (0)
+
+#define BPDQ_LAUNCH_CHECK()                     \
+  do {                                          \
+    if (hipGetLastError() != hipSuccess) return BPDQ_ERR_LAUNCH; \
+  } while (0)
+
+static inline size_t bpdq_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+static inline int bpdq_ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// bump allocator over the caller's workspace
+struct BpdqArena {
+  char* base;
+  size_t off;
+  explicit BpdqArena(void* p) : base(static_cast<char*>(p)), off(0) {}
+  template <typename T>
+  T* take(size_t n) {
+    T* r = reinterpret_cast<T*>(base + off);
+    off += bpdq_align_up(n * sizeof(T), 256);
+    return r;
+  }
+};

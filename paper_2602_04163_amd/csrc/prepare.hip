@@ -1,0 +1,394 @@
+// Step 2 of the pass: damping and U = chol(H^-1), H^-1 = U^T U with U upper triangular
+// (paper Sec. 3.1, "Quantization Error Compensation").
+//
+// Route: with Ht = H + lambda I, factor Ht = R R^T with R UPPER triangular (a Cholesky
+// factorisation that runs from the last column to the first).  Then
+// Ht^-1 = R^-T R^-1 = (R^-1)^T (R^-1), so U = R^-1: one factorisation plus one triangular
+// inverse (2/3 d^3 flops) and Ht^-1 is never formed.  Everything runs in fp64 inside the
+// workspace; the result is rounded to fp32 once, on output.
+//
+//   factor : right-looking over 64-column panels from the right: diagonal block factor +
+//            inverse in one work-group, panel R12 = A12 R22^-T, trailing update
+//            A11 -= R12 R12^T on the upper 64 x 64 tiles.
+//   invert : divide and conquer over block ranges, [R11 R12; 0 R22]^-1 =
+//            [U11, -U11 R12 U22; 0, U22]; every tree level is two launches.
+#include "common.h"
+
+namespace bpdq {
+
+constexpr int NB = 64;    // panel / tile size (fp64)
+
+// ---------------------------------------------------------------- damping ------------------
+// One work-group: dead flags, mean of the (fixed) diagonal, lambda.  scal[0] = lambda.
+__global__ __launch_bounds__(1024) void prep_diag_kernel(const float* __restrict__ H, int d,
+                                                         float damp, unsigned char* __restrict__ dead,
+                                                         double* __restrict__ scal, int* info) {
+  __shared__ double red[1024];
+  double s = 0.0;
+  for (int i = threadIdx.x; i < d; i += 1024) {
+    float h = H[(long)i * d + i];
+    const bool dd = (h == 0.f);
+    if (dead) dead[i] = dd ? 1 : 0;
+    s += dd ? 1.0 : (double)h;
+  }
+  red[threadIdx.x] = s;
+  __syncthreads();
+  for (int w = 512; w > 0; w >>= 1) {
+    if (threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    scal[0] = (double)damp * (red[0] / (double)d);
+    *info = 0;
+  }
+}
+
+// A (fp64, d x d) <- upper triangle of H with the diagonal fixed and damped; lower part 0.
+__global__ __launch_bounds__(256) void prep_load_kernel(const float* __restrict__ H, int d,
+                                                        const double* __restrict__ scal,
+                                                        double* __restrict__ A) {
+  const long n = (long)d * d;
+  const double lam = scal[0];
+  for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < n; e += (long)gridDim.x * 256) {
+    const int i = (int)(e / d), j = (int)(e % d);
+    double v = 0.0;
+    if (j >= i) {
+      const float h = H[e];
+      v = (double)h;
+      if (i == j) v = (h == 0.f ? 1.0 : v) + lam;
+    }
+    A[e] = v;
+  }
+}
+
+// ---------------------------------------------------------------- factor -------------------
+// Diagonal block [p0, p0+nb): D = R R^T (R upper), processed from the last column to the
+// first; R overwrites the block's upper triangle, R^-1 goes to Dinv (nb x nb, row-major,
+// leading dimension NB).  One work-group of 256 threads.
+__global__ __launch_bounds__(256) void potrf_rev_diag_kernel(double* __restrict__ A, int d, int p0,
+                                                             int nb, double* __restrict__ Dinv,
+                                                             int* info) {
+  __shared__ double s[NB][NB + 1];
+  __shared__ double x[NB][NB + 1];
+  const int tid = threadIdx.x;
+  for (int e = tid; e < NB * NB; e += 256) {
+    const int i = e / NB, j = e % NB;
+    double v = 0.0;
+    if (i < nb && j < nb) v = (j >= i) ? A[(long)(p0 + i) * d + p0 + j] : A[(long)(p0 + j) * d + p0 + i];
+    s[i][j] = v;
+    x[i][j] = 0.0;
+  }
+  __syncthreads();
+  for (int j = nb - 1; j >= 0; --j) {
+    if (tid == 0) {
+      double piv = s[j][j];
+      if (!(piv > 0.0)) {
+        atomicCAS(info, 0, p0 + j + 1);
+        piv = 1.0;
+      }
+      s[j][j] = sqrt(piv);
+    }
+    __syncthreads();
+    const double rjj = s[j][j];
+    if (tid < j) s[tid][j] /= rjj;
+    __syncthreads();
+    for (int e = tid; e < j * j; e += 256) {
+      const int i = e / j, i2 = e % j;
+      if (i2 >= i) s[i][i2] -= s[i][j] * s[i2][j];
+    }
+    __syncthreads();
+  }
+  // inverse of the upper triangular R: thread c solves R x = e_c by back substitution
+  if (tid < nb) {
+    const int c = tid;
+    x[c][c] = 1.0 / s[c][c];
+    for (int i = c - 1; i >= 0; --i) {
+      double acc = 0.0;
+      for (int m = i + 1; m <= c; ++m) acc += s[i][m] * x[m][c];
+      x[i][c] = -acc / s[i][i];
+    }
+  }
+  __syncthreads();
+  for (int e = tid; e < NB * NB; e += 256) {
+    const int i = e / NB, j = e % NB;
+    if (i < nb && j < nb && j >= i) A[(long)(p0 + i) * d + p0 + j] = s[i][j];
+    Dinv[e] = (i < nb && j < nb && j >= i) ? x[i][j] : 0.0;
+  }
+}
+
+// Panel above the diagonal block: R12 = A12 * R22^-T = A12 * Uinv^T, in place.
+// out[i][j] = sum_{k >= j} A12[i][k] * Uinv[j][k].  One work-group per 64 rows.
+__global__ __launch_bounds__(256) void panel_trsm_kernel(double* __restrict__ A, int d, int p0,
+                                                         int nb, const double* __restrict__ Dinv) {
+  __shared__ double sa[NB][NB + 1];
+  __shared__ double su[NB][NB + 1];
+  const int tid = threadIdx.x;
+  const int r0 = blockIdx.x * NB;
+  for (int e = tid; e < NB * NB; e += 256) {
+    const int i = e / NB, j = e % NB;
+    su[i][j] = Dinv[e];
+    sa[i][j] = (r0 + i < p0 && j < nb) ? A[(long)(r0 + i) * d + p0 + j] : 0.0;
+  }
+  __syncthreads();
+  const int tx = tid & 15, ty = tid >> 4;     // 16 x 16 threads, 4 x 4 outputs each
+  double acc[4][4] = {};
+  for (int k = 0; k < NB; ++k) {
+    double a[4], u[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) a[q] = sa[ty + 16 * q][k];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) u[q] = su[tx + 16 * q][k];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int w = 0; w < 4; ++w) acc[q][w] += a[q] * u[w];
+  }
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const int i = r0 + ty + 16 * q, j = tx + 16 * w;
+      if (i < p0 && j < nb) A[(long)i * d + p0 + j] = acc[q][w];
+    }
+}
+
+// Trailing update on the upper 64 x 64 tiles of the leading p0 x p0 block:
+// A11[i][j] -= sum_k R12[i][k] R12[j][k], k over the nb panel columns.
+__global__ __launch_bounds__(256) void syrk_trailing_kernel(double* __restrict__ A, int d, int p0,
+                                                            int nb, int nblk) {
+  __shared__ double si[NB][NB + 1];
+  __shared__ double sj[NB][NB + 1];
+  int tile = blockIdx.x, bi = 0;
+  while (tile >= nblk - bi) {
+    tile -= nblk - bi;
+    ++bi;
+  }
+  const int bj = bi + tile;
+  const int tid = threadIdx.x;
+  for (int e = tid; e < NB * NB; e += 256) {
+    const int i = e / NB, k = e % NB;
+    si[i][k] = (bi * NB + i < p0 && k < nb) ? A[(long)(bi * NB + i) * d + p0 + k] : 0.0;
+    sj[i][k] = (bj * NB + i < p0 && k < nb) ? A[(long)(bj * NB + i) * d + p0 + k] : 0.0;
+  }
+  __syncthreads();
+  const int tx = tid & 15, ty = tid >> 4;
+  double acc[4][4] = {};
+  for (int k = 0; k < NB; ++k) {
+    double a[4], b[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) a[q] = si[ty + 16 * q][k];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) b[q] = sj[tx + 16 * q][k];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int w = 0; w < 4; ++w) acc[q][w] += a[q] * b[w];
+  }
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const int i = bi * NB + ty + 16 * q, j = bj * NB + tx + 16 * w;
+      if (i < p0 && j < p0 && j >= i) A[(long)i * d + j] -= acc[q][w];
+    }
+}
+
+// ---------------------------------------------------------------- invert -------------------
+// Diagonal blocks of A <- R_pp^-1 (upper), strictly lower part of each block <- 0.
+__global__ __launch_bounds__(256) void put_diag_inverse_kernel(double* __restrict__ A, int d,
+                                                               const double* __restrict__ Dinv) {
+  const int p0 = blockIdx.x * NB;
+  const double* src = Dinv + (long)blockIdx.x * NB * NB;
+  for (int e = threadIdx.x; e < NB * NB; e += 256) {
+    const int i = e / NB, j = e % NB;
+    if (p0 + i < d && p0 + j < d) A[(long)(p0 + i) * d + p0 + j] = src[e];
+  }
+}
+
+// Node `node` of tree depth `depth` over the block range [0, P): ranges are halved
+// (left half gets the extra block).  Returns false if the path ends in a leaf earlier.
+__device__ __forceinline__ bool tree_node(int P, int depth, int node, int& lo, int& mid, int& hi) {
+  lo = 0;
+  hi = P;
+  for (int l = depth - 1; l >= 0; --l) {
+    if (hi - lo < 2) return false;
+    const int m = lo + (hi - lo + 1) / 2;
+    if ((node >> l) & 1) lo = m; else hi = m;
+  }
+  if (hi - lo < 2) return false;
+  mid = lo + (hi - lo + 1) / 2;
+  return true;
+}
+
+// One 64 x 64 output tile of C = op(A) * op(B) in fp64, 256 threads, 4 x 4 per thread.
+// MODE 1: tmp = R12 * U22      (B upper triangular: k-tiles 0..tj, diagonal tile masked)
+// MODE 2: A12 = -U11 * tmp     (A upper triangular: k-tiles ti..M-1, diagonal tile masked)
+template <int MODE>
+__global__ __launch_bounds__(256) void tri_inverse_level_kernel(double* __restrict__ A, int d,
+                                                                double* __restrict__ tmp, int ldt,
+                                                                int P, int depth) {
+  __shared__ double sa[NB][NB + 1];
+  __shared__ double sb[NB][NB + 1];
+  int lo, mid, hi;
+  if (!tree_node(P, depth, blockIdx.z, lo, mid, hi)) return;
+  const int Mb = mid - lo, Nb = hi - mid;        // in blocks
+  const int ti = blockIdx.y, tj = blockIdx.x;
+  if (ti >= Mb || tj >= Nb) return;
+  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+  const int row0 = (lo + ti) * NB;               // global rows of the output tile
+  const int col0 = (mid + tj) * NB;              // global cols of the output tile (in A)
+  double acc[4][4] = {};
+  const int kb_begin = (MODE == 1) ? 0 : ti;
+  const int kb_end = (MODE == 1) ? tj + 1 : Mb;
+  for (int kb = kb_begin; kb < kb_end; ++kb) {
+    for (int e = tid; e < NB * NB; e += 256) {
+      const int i = e / NB, j = e % NB;
+      double va, vb;
+      if (MODE == 1) {
+        // A operand: R12[row0+i][mid*NB + kb*NB + j];  B operand: U22[(mid+kb)*NB+i][col0+j]
+        const int gr = row0 + i, gc = (mid + kb) * NB + j;
+        va = (gr < d && gc < d) ? A[(long)gr * d + gc] : 0.0;
+        const int br = (mid + kb) * NB + i, bc = col0 + j;
+        vb = (br < d && bc < d && br <= bc) ? A[(long)br * d + bc] : 0.0;
+      } else {
+        // A operand: U11[row0+i][(lo+kb)*NB + j];  B operand: tmp[(lo+kb)*NB+i][tj*NB+j]
+        const int gr = row0 + i, gc = (lo + kb) * NB + j;
+        va = (gr < d && gc < d && gr <= gc) ? A[(long)gr * d + gc] : 0.0;
+        const int br = (lo + kb) * NB + i;
+        vb = (br < d) ? tmp[(long)br * ldt + tj * NB + j] : 0.0;
+      }
+      sa[i][j] = va;
+      sb[i][j] = vb;
+    }
+    __syncthreads();
+    for (int k = 0; k < NB; ++k) {
+      double a[4], b[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) a[q] = sa[ty + 16 * q][k];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) b[q] = sb[k][tx + 16 * q];
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int w = 0; w < 4; ++w) acc[q][w] += a[q] * b[w];
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const int i = row0 + ty + 16 * q, jl = tx + 16 * w;
+      if (i >= d) continue;
+      if (MODE == 1) {
+        tmp[(long)i * ldt + tj * NB + jl] = acc[q][w];
+      } else if (col0 + jl < d) {
+        A[(long)i * d + col0 + jl] = -acc[q][w];
+      }
+    }
+}
+
+// U (fp32) <- upper triangle of A, zeros below.
+__global__ __launch_bounds__(256) void prep_store_kernel(const double* __restrict__ A, int d,
+                                                         float* __restrict__ U) {
+  const long n = (long)d * d;
+  for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < n; e += (long)gridDim.x * 256) {
+    const int i = (int)(e / d), j = (int)(e % d);
+    U[e] = (j >= i) ? (float)A[e] : 0.f;
+  }
+}
+
+static int tree_depth(int P) {   // number of levels that contain at least one internal node
+  int depth = 0, width = P;
+  while (width >= 2) {
+    width = (width + 1) / 2;
+    ++depth;
+  }
+  return depth;
+}
+
+struct PrepLayout {
+  size_t a_off, tmp_off, dinv_off, scal_off, total;
+  int P, ldt;
+};
+
+static PrepLayout prep_layout(int d) {
+  PrepLayout L;
+  L.P = bpdq_ceil_div(d, NB);
+  L.ldt = ((L.P + 1) / 2) * NB;
+  size_t off = 0;
+  L.a_off = off;    off += bpdq_align_up((size_t)d * d * sizeof(double), 256);
+  L.tmp_off = off;  off += bpdq_align_up((size_t)d * L.ldt * sizeof(double), 256);
+  L.dinv_off = off; off += bpdq_align_up((size_t)L.P * NB * NB * sizeof(double), 256);
+  L.scal_off = off; off += 256;
+  L.total = off;
+  return L;
+}
+
+}  // namespace bpdq
+
+using namespace bpdq;
+
+extern "C" size_t bpdq_prepare_workspace_bytes(int d_in) {
+  if (d_in <= 0) return 0;
+  return prep_layout(d_in).total;
+}
+
+extern "C" int bpdq_prepare(const float* H, int d_in, float damp, float* U, unsigned char* dead,
+                            int* info, void* ws, size_t ws_bytes, void* stream_) {
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  if (!H) return -1;
+  if (d_in <= 0) return -2;
+  if (!(damp >= 0.f)) return -3;
+  if (!U) return -4;
+  if (!info) return -6;
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255)) return -7;
+  const PrepLayout L = prep_layout(d_in);
+  if (ws_bytes < L.total) return -8;
+  char* base = static_cast<char*>(ws);
+  double* A = reinterpret_cast<double*>(base + L.a_off);
+  double* tmp = reinterpret_cast<double*>(base + L.tmp_off);
+  double* Dinv = reinterpret_cast<double*>(base + L.dinv_off);
+  double* scal = reinterpret_cast<double*>(base + L.scal_off);
+  const int d = d_in, P = L.P;
+
+  hipLaunchKernelGGL(prep_diag_kernel, dim3(1), dim3(1024), 0, stream, H, d, damp, dead, scal, info);
+  BPDQ_LAUNCH_CHECK();
+  const int grid_el = (int)((((long)d * d + 255) / 256) < 65536 ? (((long)d * d + 255) / 256) : 65536);
+  hipLaunchKernelGGL(prep_load_kernel, dim3(grid_el), dim3(256), 0, stream, H, d, scal, A);
+  BPDQ_LAUNCH_CHECK();
+
+  for (int p = P - 1; p >= 0; --p) {
+    const int p0 = p * NB;
+    const int nb = (d - p0 < NB) ? d - p0 : NB;
+    hipLaunchKernelGGL(potrf_rev_diag_kernel, dim3(1), dim3(256), 0, stream, A, d, p0, nb,
+                       Dinv + (size_t)p * NB * NB, info);
+    BPDQ_LAUNCH_CHECK();
+    if (p > 0) {
+      hipLaunchKernelGGL(panel_trsm_kernel, dim3(p), dim3(256), 0, stream, A, d, p0, nb,
+                         Dinv + (size_t)p * NB * NB);
+      BPDQ_LAUNCH_CHECK();
+      hipLaunchKernelGGL(syrk_trailing_kernel, dim3(p * (p + 1) / 2), dim3(256), 0, stream, A, d,
+                         p0, nb, p);
+      BPDQ_LAUNCH_CHECK();
+    }
+  }
+
+  hipLaunchKernelGGL(put_diag_inverse_kernel, dim3(P), dim3(256), 0, stream, A, d, Dinv);
+  BPDQ_LAUNCH_CHECK();
+  const int depth = tree_depth(P);
+  for (int dd = depth - 1; dd >= 0; --dd) {
+    // at depth dd a node spans at most ceil(P / 2^dd) blocks
+    int span = P;
+    for (int l = 0; l < dd; ++l) span = (span + 1) / 2;
+    const int half = (span + 1) / 2;
+    dim3 grid(half, half, 1 << dd);
+    hipLaunchKernelGGL(tri_inverse_level_kernel<1>, grid, dim3(256), 0, stream, A, d, tmp, L.ldt, P, dd);
+    BPDQ_LAUNCH_CHECK();
+    hipLaunchKernelGGL(tri_inverse_level_kernel<2>, grid, dim3(256), 0, stream, A, d, tmp, L.ldt, P, dd);
+    BPDQ_LAUNCH_CHECK();
+  }
+  hipLaunchKernelGGL(prep_store_kernel, dim3(grid_el), dim3(256), 0, stream, A, d, U);
+  BPDQ_LAUNCH_CHECK();
+  return 0;
+}
