@@ -29,11 +29,13 @@ def parse():
     ap.add_argument("--tokens-per-call", type=int, default=0,
                     help="tokens per bpdq_hessian_accumulate call (0 = all tokens in one call)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB -> 1 GiB elementwise kernel (scale for HBM counters)")
     ap.add_argument("--phases-only", default="", help="comma list of hessian,prepare,quantize (profiling)")
     return ap.parse_args()
 
 
-def cpu_baseline(wl, W_cpu, scales_cpu, n_tok_sub=8192, rows_sub=128):
+def cpu_baseline(wl, W_cpu, scales_cpu, n_tok_sub=65536, rows_sub=1024):
     """The oracle, as it stands, on a bounded sample of the same workload; its time is scaled
     linearly to the full layer (tokens for the Hessian, rows for the sweep)."""
     import numpy as np
@@ -139,6 +141,12 @@ def main():
         phases = ["hessian", "prepare", "quantize"]
         step(False)
         phases = saved
+    if args.calibrate_copy:
+        src = X.view(-1)[: (1 << 28)]                 # 2^28 floats = 1 GiB read, 1 GiB written
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 2.0, out=dst)
+        del dst
     for _ in range(args.warmup):
         step(False)
     torch.cuda.synchronize()
