@@ -7,9 +7,9 @@
 // inverse (2/3 d^3 flops) and Ht^-1 is never formed.  Everything runs in fp64 inside the
 // workspace; the result is rounded to fp32 once, on output.
 //
-//   factor : right-looking over 64-column panels from the right: diagonal block factor +
-//            inverse in one work-group, panel R12 = A12 R22^-T, trailing update
-//            A11 -= R12 R12^T on the upper 64 x 64 tiles.
+//   factor : right-looking over 64-column panels from the right: every panel work-group factors
+//            the diagonal block in registers and solves its 64 rows of R12 R22^T = A12, then the
+//            trailing update A11 -= R12 R12^T runs on the upper 64 x 64 tiles.
 //   invert : divide and conquer over block ranges, [R11 R12; 0 R22]^-1 =
 //            [U11, -U11 R12 U22; 0, U22]; every tree level is two launches.
 #include "common.h"
@@ -62,94 +62,143 @@ __global__ __launch_bounds__(256) void prep_load_kernel(const float* __restrict_
 }
 
 // ---------------------------------------------------------------- factor -------------------
-// Diagonal block [p0, p0+nb): D = R R^T (R upper), processed from the last column to the
-// first; R overwrites the block's upper triangle, R^-1 goes to Dinv (nb x nb, row-major,
-// leading dimension NB).  One work-group of 256 threads.
-__global__ __launch_bounds__(256) void potrf_rev_diag_kernel(double* __restrict__ A, int d, int p0,
-                                                             int nb, double* __restrict__ Dinv,
-                                                             int* info) {
-  __shared__ double s[NB][NB + 1];
-  __shared__ double x[NB][NB + 1];
-  const int tid = threadIdx.x;
+// 1 / x in fp64: hardware estimate + two Newton steps (the pivot reciprocal sits on the critical
+// path of every column step).
+__device__ __forceinline__ double fast_rcp(double x) {
+  double r = __builtin_amdgcn_rcp(x);
+  r = fma(fma(-x, r, 1.0), r, r);
+  r = fma(fma(-x, r, 1.0), r, r);
+  return r;
+}
+
+// Panel step of the reversed Cholesky, one work-group (256 threads) per 64 rows of the panel.
+//   (1) every work-group factors the 64 x 64 diagonal block D = R R^T (R upper, columns taken
+//       from the last to the first) for itself: thread (ty, tx) keeps the 4 x 4 sub-block
+//       rows 4ty.., cols 4tx.. in registers; per column one LDS broadcast of the current column,
+//       one barrier, one reciprocal and a rank-1 update  a -= col col^T / pivot.
+//   (2) rows [64 b, 64 b + 64) of the panel above the block: X R^T = A12 solved by substitution,
+//       one thread per row, the row held in registers.
+// Work-group 0 also writes R into the diagonal block and reports a non-positive pivot.
+// Launch with max(p, 1) work-groups, p = number of 64-row blocks above the diagonal block.
+__global__ __launch_bounds__(256) void panel_factor_kernel(double* __restrict__ A, int d, int p0,
+                                                           int nb, int n_above, int* info) {
+  __shared__ double sR[NB][NB + 1];     // R (upper) of the diagonal block
+  __shared__ double sA[NB][NB + 1];     // panel tile of this work-group
+  __shared__ double col[2][NB];
+  __shared__ double sInvD[NB];
+  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+
+  double a[4][4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int i = 4 * ty + r, j = 4 * tx + c;
+      double v = (i == j) ? 1.0 : 0.0;              // identity padding of a ragged last block
+      if (i < nb && j < nb)
+        v = (j >= i) ? A[(long)(p0 + i) * d + p0 + j] : A[(long)(p0 + j) * d + p0 + i];
+      a[r][c] = v;
+    }
+  // panel tile (coalesced), used after the factorisation
+  const int r0 = blockIdx.x * NB;
+  if (n_above > 0) {
+    for (int e = tid; e < NB * NB; e += 256) {
+      const int i = e / NB, j = e % NB;
+      sA[i][j] = (r0 + i < p0 && j < nb) ? A[(long)(r0 + i) * d + p0 + j] : 0.0;
+    }
+  }
+
+#pragma unroll 1
+  for (int jb = NB / 4 - 1; jb >= 0; --jb) {
+#pragma unroll
+    for (int jj = 3; jj >= 0; --jj) {
+      const int j = 4 * jb + jj;
+      double* cbuf = col[j & 1];
+      if (tx == jb) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) cbuf[4 * ty + r] = a[r][jj];
+      }
+      __syncthreads();
+      double piv = cbuf[j];
+      if (!(piv > 0.0)) {
+        if (tid == 0 && blockIdx.x == 0) atomicCAS(info, 0, p0 + j + 1);
+        piv = 1.0;
+      }
+      const double ip = fast_rcp(piv);
+      double ci[4], cj[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) ci[r] = cbuf[4 * ty + r] * ip;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) cj[c] = cbuf[4 * tx + c];
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) a[r][c] = fma(-ci[r], cj[c], a[r][c]);
+      if (tid < NB) {
+        const double rs = 1.0 / sqrt(piv);
+        sR[tid][j] = (tid <= j) ? cbuf[tid] * rs : 0.0;
+        if (tid == j) sInvD[j] = rs;
+      }
+    }
+  }
+  __syncthreads();
+  if (blockIdx.x == 0) {
+    for (int e = tid; e < NB * NB; e += 256) {
+      const int i = e / NB, j = e % NB;
+      if (i < nb && j < nb && j >= i) A[(long)(p0 + i) * d + p0 + j] = sR[i][j];
+    }
+  }
+  if (n_above == 0) return;
+
+  // (2) X R^T = A12  =>  X[j] = (A12[j] - sum_{k>j} X[k] R[j][k]) / R[j][j], j = 63 .. 0
+  if (tid < NB) {
+    double x[NB];
+#pragma unroll
+    for (int j = NB - 1; j >= 0; --j) {
+      double v = sA[tid][j];
+#pragma unroll
+      for (int k = j + 1; k < NB; ++k) v = fma(-x[k], sR[j][k], v);
+      x[j] = v * sInvD[j];
+    }
+#pragma unroll
+    for (int j = 0; j < NB; ++j) sA[tid][j] = x[j];
+  }
+  __syncthreads();
   for (int e = tid; e < NB * NB; e += 256) {
     const int i = e / NB, j = e % NB;
-    double v = 0.0;
-    if (i < nb && j < nb) v = (j >= i) ? A[(long)(p0 + i) * d + p0 + j] : A[(long)(p0 + j) * d + p0 + i];
+    if (r0 + i < p0 && j < nb) A[(long)(r0 + i) * d + p0 + j] = sA[i][j];
+  }
+}
+
+// Inverses of all diagonal blocks of R at once (one work-group per block, thread c solves
+// R x = e_c by back substitution).  Dinv[p] is NB x NB row-major, zero below the diagonal.
+__global__ __launch_bounds__(64) void diag_inverse_kernel(const double* __restrict__ A, int d,
+                                                          double* __restrict__ Dinv) {
+  __shared__ double s[NB][NB + 1];
+  __shared__ double x[NB][NB + 1];
+  const int p0 = blockIdx.x * NB;
+  const int nb = (d - p0 < NB) ? d - p0 : NB;
+  const int c = threadIdx.x;
+  for (int e = c; e < NB * NB; e += 64) {
+    const int i = e / NB, j = e % NB;
+    double v = (i == j) ? 1.0 : 0.0;
+    if (i < nb && j < nb && j >= i) v = A[(long)(p0 + i) * d + p0 + j];
     s[i][j] = v;
     x[i][j] = 0.0;
   }
   __syncthreads();
-  for (int j = nb - 1; j >= 0; --j) {
-    if (tid == 0) {
-      double piv = s[j][j];
-      if (!(piv > 0.0)) {
-        atomicCAS(info, 0, p0 + j + 1);
-        piv = 1.0;
-      }
-      s[j][j] = sqrt(piv);
-    }
-    __syncthreads();
-    const double rjj = s[j][j];
-    if (tid < j) s[tid][j] /= rjj;
-    __syncthreads();
-    for (int e = tid; e < j * j; e += 256) {
-      const int i = e / j, i2 = e % j;
-      if (i2 >= i) s[i][i2] -= s[i][j] * s[i2][j];
-    }
-    __syncthreads();
-  }
-  // inverse of the upper triangular R: thread c solves R x = e_c by back substitution
-  if (tid < nb) {
-    const int c = tid;
-    x[c][c] = 1.0 / s[c][c];
-    for (int i = c - 1; i >= 0; --i) {
-      double acc = 0.0;
-      for (int m = i + 1; m <= c; ++m) acc += s[i][m] * x[m][c];
-      x[i][c] = -acc / s[i][i];
-    }
+  x[c][c] = 1.0 / s[c][c];
+  for (int i = c - 1; i >= 0; --i) {
+    double acc = 0.0;
+    for (int m = i + 1; m <= c; ++m) acc += s[i][m] * x[m][c];
+    x[i][c] = -acc / s[i][i];
   }
   __syncthreads();
-  for (int e = tid; e < NB * NB; e += 256) {
+  double* out = Dinv + (long)blockIdx.x * NB * NB;
+  for (int e = c; e < NB * NB; e += 64) {
     const int i = e / NB, j = e % NB;
-    if (i < nb && j < nb && j >= i) A[(long)(p0 + i) * d + p0 + j] = s[i][j];
-    Dinv[e] = (i < nb && j < nb && j >= i) ? x[i][j] : 0.0;
+    out[e] = (i < nb && j < nb && j >= i) ? x[i][j] : 0.0;
   }
-}
-
-// Panel above the diagonal block: R12 = A12 * R22^-T = A12 * Uinv^T, in place.
-// out[i][j] = sum_{k >= j} A12[i][k] * Uinv[j][k].  One work-group per 64 rows.
-__global__ __launch_bounds__(256) void panel_trsm_kernel(double* __restrict__ A, int d, int p0,
-                                                         int nb, const double* __restrict__ Dinv) {
-  __shared__ double sa[NB][NB + 1];
-  __shared__ double su[NB][NB + 1];
-  const int tid = threadIdx.x;
-  const int r0 = blockIdx.x * NB;
-  for (int e = tid; e < NB * NB; e += 256) {
-    const int i = e / NB, j = e % NB;
-    su[i][j] = Dinv[e];
-    sa[i][j] = (r0 + i < p0 && j < nb) ? A[(long)(r0 + i) * d + p0 + j] : 0.0;
-  }
-  __syncthreads();
-  const int tx = tid & 15, ty = tid >> 4;     // 16 x 16 threads, 4 x 4 outputs each
-  double acc[4][4] = {};
-  for (int k = 0; k < NB; ++k) {
-    double a[4], u[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) a[q] = sa[ty + 16 * q][k];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) u[q] = su[tx + 16 * q][k];
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-#pragma unroll
-      for (int w = 0; w < 4; ++w) acc[q][w] += a[q] * u[w];
-  }
-#pragma unroll
-  for (int q = 0; q < 4; ++q)
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const int i = r0 + ty + 16 * q, j = tx + 16 * w;
-      if (i < p0 && j < nb) A[(long)i * d + p0 + j] = acc[q][w];
-    }
 }
 
 // Trailing update on the upper 64 x 64 tiles of the leading p0 x p0 block:
@@ -361,19 +410,18 @@ extern "C" int bpdq_prepare(const float* H, int d_in, float damp, float* U, unsi
   for (int p = P - 1; p >= 0; --p) {
     const int p0 = p * NB;
     const int nb = (d - p0 < NB) ? d - p0 : NB;
-    hipLaunchKernelGGL(potrf_rev_diag_kernel, dim3(1), dim3(256), 0, stream, A, d, p0, nb,
-                       Dinv + (size_t)p * NB * NB, info);
+    hipLaunchKernelGGL(panel_factor_kernel, dim3(p > 0 ? p : 1), dim3(256), 0, stream, A, d, p0, nb,
+                       p, info);
     BPDQ_LAUNCH_CHECK();
     if (p > 0) {
-      hipLaunchKernelGGL(panel_trsm_kernel, dim3(p), dim3(256), 0, stream, A, d, p0, nb,
-                         Dinv + (size_t)p * NB * NB);
-      BPDQ_LAUNCH_CHECK();
       hipLaunchKernelGGL(syrk_trailing_kernel, dim3(p * (p + 1) / 2), dim3(256), 0, stream, A, d,
                          p0, nb, p);
       BPDQ_LAUNCH_CHECK();
     }
   }
 
+  hipLaunchKernelGGL(diag_inverse_kernel, dim3(P), dim3(64), 0, stream, A, d, Dinv);
+  BPDQ_LAUNCH_CHECK();
   hipLaunchKernelGGL(put_diag_inverse_kernel, dim3(P), dim3(256), 0, stream, A, d, Dinv);
   BPDQ_LAUNCH_CHECK();
   const int depth = tree_depth(P);
