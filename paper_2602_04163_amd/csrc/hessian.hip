@@ -19,7 +19,7 @@ struct HessPlan {
 
 static HessPlan plan_hessian(int n_tok, int d_in) {
   HessPlan p;
-  p.nb = bpdq_ceil_div(d_in, kTileM);
+  p.nb = bpdq_ceil_div(d_in, HessGemm::kTileM);
   p.n_tiles = p.nb * (p.nb + 1) / 2;
   p.S = 1;
   p.k_per = (int)bpdq_align_up((size_t)(n_tok > 0 ? n_tok : 1), kStageK);
@@ -51,7 +51,7 @@ __device__ __forceinline__ void decode_upper_tile(int tile, int nb, int& bi, int
   bj = bi + tile;
 }
 
-__global__ __launch_bounds__(kGemmThreads) void hess_syrk_f32_kernel(
+__global__ __launch_bounds__(HessGemm::kThreads) void hess_syrk_f32_kernel(
     const float* __restrict__ X, int n_tok, int d, long ldx, float scale, float* __restrict__ H,
     float* __restrict__ partial, int nb, int n_tiles, int S, int k_per) {
   const int item = blockIdx.x;
@@ -60,22 +60,22 @@ __global__ __launch_bounds__(kGemmThreads) void hess_syrk_f32_kernel(
   decode_upper_tile(item % n_tiles, nb, bi, bj);
   const int k_begin = split * k_per;
   const int k_end = min(n_tok, k_begin + k_per);
-  TileAcc acc;
-  zero_acc(acc);
+  HessGemm::Acc acc;
+  HessGemm::zero(acc);
   if (bi == bj) {
-    mfma_kmajor_tile<true>(X, ldx, bi * kTileM, d, X, ldx, bj * kTileN, d, k_begin, k_end, acc);
+    HessGemm::run<true>(X, ldx, bi * HessGemm::kTileM, d, X, ldx, bj * HessGemm::kTileN, d, k_begin, k_end, acc);
   } else {
-    mfma_kmajor_tile<false>(X, ldx, bi * kTileM, d, X, ldx, bj * kTileN, d, k_begin, k_end, acc);
+    HessGemm::run<false>(X, ldx, bi * HessGemm::kTileM, d, X, ldx, bj * HessGemm::kTileN, d, k_begin, k_end, acc);
   }
   if (S == 1) {
-    const int r0 = bi * kTileM, c0 = bj * kTileN;
-    for_each_acc(acc, [&](int row, int col, float v) {
+    const int r0 = bi * HessGemm::kTileM, c0 = bj * HessGemm::kTileN;
+    HessGemm::for_each(acc, [&](int row, int col, float v) {
       const int r = r0 + row, c = c0 + col;
       if (r < d && c < d) H[(long)r * d + c] += scale * v;
     });
   } else {
-    float* out = partial + (long)item * (kTileM * kTileN);
-    for_each_acc(acc, [&](int row, int col, float v) { out[row * kTileN + col] = v; });
+    float* out = partial + (long)item * (HessGemm::kTileM * HessGemm::kTileN);
+    HessGemm::for_each(acc, [&](int row, int col, float v) { out[row * HessGemm::kTileN + col] = v; });
   }
 }
 
@@ -87,13 +87,13 @@ __global__ __launch_bounds__(256) void hess_reduce_kernel(const float* __restric
   const int e = ((blockIdx.x & 63) * 256 + threadIdx.x) * 4;
   int bi, bj;
   decode_upper_tile(tile, nb, bi, bj);
-  const int r = bi * kTileM + e / kTileN;
-  const int c = bj * kTileN + e % kTileN;
+  const int r = bi * HessGemm::kTileM + e / HessGemm::kTileN;
+  const int c = bj * HessGemm::kTileN + e % HessGemm::kTileN;
   if (r >= d || c >= d) return;
   float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
   for (int sp = 0; sp < S; ++sp) {
     const float4 v = *reinterpret_cast<const float4*>(
-        partial + ((long)sp * n_tiles + tile) * (kTileM * kTileN) + e);
+        partial + ((long)sp * n_tiles + tile) * (HessGemm::kTileM * HessGemm::kTileN) + e);
     s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
   }
   float4* h = reinterpret_cast<float4*>(H + (long)r * d + c);
@@ -127,7 +127,7 @@ extern "C" size_t bpdq_hessian_workspace_bytes(int n_tok, int d_in) {
   if (n_tok <= 0 || d_in <= 0) return 0;
   const HessPlan p = plan_hessian(n_tok, d_in);
   if (p.S == 1) return 0;
-  return (size_t)p.S * p.n_tiles * kTileM * kTileN * sizeof(float);
+  return (size_t)p.S * p.n_tiles * HessGemm::kTileM * HessGemm::kTileN * sizeof(float);
 }
 
 extern "C" int bpdq_hessian_accumulate(const float* Xc, int n_tok, int d_in, int ldx, float scale,
@@ -141,18 +141,18 @@ extern "C" int bpdq_hessian_accumulate(const float* Xc, int n_tok, int d_in, int
   if (!H || (reinterpret_cast<uintptr_t>(H) & 15)) return -6;
   if (n_tok > 0) {
     const HessPlan p = plan_hessian(n_tok, d_in);
-    const size_t need = p.S == 1 ? 0 : (size_t)p.S * p.n_tiles * kTileM * kTileN * sizeof(float);
+    const size_t need = p.S == 1 ? 0 : (size_t)p.S * p.n_tiles * HessGemm::kTileM * HessGemm::kTileN * sizeof(float);
     if (need > 0 && (!ws || (reinterpret_cast<uintptr_t>(ws) & 15))) return -8;
     if (ws_bytes < need) return -9;
     static bool attr_set = false;
     if (!attr_set) {
       BPDQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(hess_syrk_f32_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)kGemmLdsBytes));
+                                       (int)HessGemm::kLdsBytes));
       attr_set = true;
     }
-    hipLaunchKernelGGL(hess_syrk_f32_kernel, dim3(p.n_tiles * p.S), dim3(kGemmThreads),
-                       kGemmLdsBytes, stream, Xc, n_tok, d_in, (long)ldx, scale, H,
+    hipLaunchKernelGGL(hess_syrk_f32_kernel, dim3(p.n_tiles * p.S), dim3(HessGemm::kThreads),
+                       HessGemm::kLdsBytes, stream, Xc, n_tok, d_in, (long)ldx, scale, H,
                        static_cast<float*>(ws), p.nb, p.n_tiles, p.S, p.k_per);
     BPDQ_LAUNCH_CHECK();
     if (p.S > 1) {

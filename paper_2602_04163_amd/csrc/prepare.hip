@@ -135,11 +135,18 @@ __global__ __launch_bounds__(256) void panel_factor_kernel(double* __restrict__ 
 #pragma unroll
         for (int c = 0; c < 4; ++c) a[r][c] = fma(-ci[r], cj[c], a[r][c]);
       if (tid < NB) {
-        const double rs = 1.0 / sqrt(piv);
-        sR[tid][j] = (tid <= j) ? cbuf[tid] * rs : 0.0;
-        if (tid == j) sInvD[j] = rs;
+        sR[tid][j] = (tid <= j) ? cbuf[tid] : 0.0;     // unscaled column; scaled after the loop
+        if (tid == j) sInvD[j] = piv;
       }
     }
+  }
+  __syncthreads();
+  // R[:, j] = column_j / sqrt(pivot_j): the square roots are taken once, off the critical path
+  if (tid < NB) sInvD[tid] = 1.0 / sqrt(sInvD[tid]);
+  __syncthreads();
+  for (int e = tid; e < NB * NB; e += 256) {
+    const int i = e / NB, j = e % NB;
+    sR[i][j] *= sInvD[j];
   }
   __syncthreads();
   if (blockIdx.x == 0) {
@@ -150,15 +157,17 @@ __global__ __launch_bounds__(256) void panel_factor_kernel(double* __restrict__ 
   }
   if (n_above == 0) return;
 
-  // (2) X R^T = A12  =>  X[j] = (A12[j] - sum_{k>j} X[k] R[j][k]) / R[j][j], j = 63 .. 0
+  // (2) X R^T = A12 by substitution from the last column: x_j = rem_j / R_jj, then
+  //     rem_k -= x_j R[k][j] for every k < j (independent updates: no serial dot product)
   if (tid < NB) {
     double x[NB];
 #pragma unroll
-    for (int j = NB - 1; j >= 0; --j) {
-      double v = sA[tid][j];
+    for (int j = 0; j < NB; ++j) x[j] = sA[tid][j];
 #pragma unroll
-      for (int k = j + 1; k < NB; ++k) v = fma(-x[k], sR[j][k], v);
-      x[j] = v * sInvD[j];
+    for (int j = NB - 1; j >= 0; --j) {
+      x[j] *= sInvD[j];
+#pragma unroll
+      for (int k = 0; k < j; ++k) x[k] = fma(-x[j], sR[k][j], x[k]);
     }
 #pragma unroll
     for (int j = 0; j < NB; ++j) sA[tid][j] = x[j];
@@ -201,6 +210,61 @@ __global__ __launch_bounds__(64) void diag_inverse_kernel(const double* __restri
   }
 }
 
+// 64 x 64 x 64 fp64 product on the matrix cores for a 256-thread work-group: wavefront w owns
+// the 32 x 32 quadrant (w / 2, w % 2) as 2 x 2 tiles of v_mfma_f64_16x16x4_f64.
+//   A operand: lane l holds A[m = l % 16][k = l / 16];  B operand: B[k = l / 16][n = l % 16];
+//   D: register r of lane l is D[4 * r + l / 16][l % 16].
+// sa is [m][k]; sb is [k][n], or [n][k] when B_T (second operand given by rows, as in a SYRK).
+// With the 65-double row pitch every 16-lane group reads 16 distinct bank pairs.
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+
+struct Quad64 {
+  f64x4 c[2][2];
+};
+
+__device__ __forceinline__ void quad_zero(Quad64& q) {
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) q.c[i][j] = (f64x4){0.0, 0.0, 0.0, 0.0};
+}
+
+template <bool B_T>
+__device__ __forceinline__ void quad_mfma_64(const double (*sa)[NB + 1], const double (*sb)[NB + 1],
+                                             Quad64& q) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int m0 = (w >> 1) * 32 + (lane & 15), n0 = (w & 1) * 32 + (lane & 15);
+  const int kq = lane >> 4;
+#pragma unroll 4
+  for (int k0 = 0; k0 < NB; k0 += 4) {
+    const int k = k0 + kq;
+    double a[2], b[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) a[i] = sa[m0 + 16 * i][k];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) b[j] = B_T ? sb[n0 + 16 * j][k] : sb[k][n0 + 16 * j];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        q.c[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], q.c[i][j], 0, 0, 0);
+  }
+}
+
+// f(row, col, value) over this lane's 16 results, row / col inside the 64 x 64 tile
+template <typename F>
+__device__ __forceinline__ void quad_for_each(const Quad64& q, F f) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        f((w >> 1) * 32 + 16 * i + 4 * r + (lane >> 4), (w & 1) * 32 + 16 * j + (lane & 15),
+          q.c[i][j][r]);
+}
+
 // Trailing update on the upper 64 x 64 tiles of the leading p0 x p0 block:
 // A11[i][j] -= sum_k R12[i][k] R12[j][k], k over the nb panel columns.
 __global__ __launch_bounds__(256) void syrk_trailing_kernel(double* __restrict__ A, int d, int p0,
@@ -220,26 +284,13 @@ __global__ __launch_bounds__(256) void syrk_trailing_kernel(double* __restrict__
     sj[i][k] = (bj * NB + i < p0 && k < nb) ? A[(long)(bj * NB + i) * d + p0 + k] : 0.0;
   }
   __syncthreads();
-  const int tx = tid & 15, ty = tid >> 4;
-  double acc[4][4] = {};
-  for (int k = 0; k < NB; ++k) {
-    double a[4], b[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) a[q] = si[ty + 16 * q][k];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) b[q] = sj[tx + 16 * q][k];
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-#pragma unroll
-      for (int w = 0; w < 4; ++w) acc[q][w] += a[q] * b[w];
-  }
-#pragma unroll
-  for (int q = 0; q < 4; ++q)
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const int i = bi * NB + ty + 16 * q, j = bj * NB + tx + 16 * w;
-      if (i < p0 && j < p0 && j >= i) A[(long)i * d + j] -= acc[q][w];
-    }
+  Quad64 q;
+  quad_zero(q);
+  quad_mfma_64<true>(si, sj, q);
+  quad_for_each(q, [&](int r, int c, double v) {
+    const int i = bi * NB + r, j = bj * NB + c;
+    if (i < p0 && j < p0 && j >= i) A[(long)i * d + j] -= v;
+  });
 }
 
 // ---------------------------------------------------------------- invert -------------------
@@ -283,10 +334,11 @@ __global__ __launch_bounds__(256) void tri_inverse_level_kernel(double* __restri
   const int Mb = mid - lo, Nb = hi - mid;        // in blocks
   const int ti = blockIdx.y, tj = blockIdx.x;
   if (ti >= Mb || tj >= Nb) return;
-  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+  const int tid = threadIdx.x;
   const int row0 = (lo + ti) * NB;               // global rows of the output tile
   const int col0 = (mid + tj) * NB;              // global cols of the output tile (in A)
-  double acc[4][4] = {};
+  Quad64 q;
+  quad_zero(q);
   const int kb_begin = (MODE == 1) ? 0 : ti;
   const int kb_end = (MODE == 1) ? tj + 1 : Mb;
   for (int kb = kb_begin; kb < kb_end; ++kb) {
@@ -310,31 +362,18 @@ __global__ __launch_bounds__(256) void tri_inverse_level_kernel(double* __restri
       sb[i][j] = vb;
     }
     __syncthreads();
-    for (int k = 0; k < NB; ++k) {
-      double a[4], b[4];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) a[q] = sa[ty + 16 * q][k];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) b[q] = sb[k][tx + 16 * q];
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-#pragma unroll
-        for (int w = 0; w < 4; ++w) acc[q][w] += a[q] * b[w];
-    }
+    quad_mfma_64<false>(sa, sb, q);
     __syncthreads();
   }
-#pragma unroll
-  for (int q = 0; q < 4; ++q)
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const int i = row0 + ty + 16 * q, jl = tx + 16 * w;
-      if (i >= d) continue;
-      if (MODE == 1) {
-        tmp[(long)i * ldt + tj * NB + jl] = acc[q][w];
-      } else if (col0 + jl < d) {
-        A[(long)i * d + col0 + jl] = -acc[q][w];
-      }
+  quad_for_each(q, [&](int r, int c, double v) {
+    const int i = row0 + r;
+    if (i >= d) return;
+    if (MODE == 1) {
+      tmp[(long)i * ldt + tj * NB + c] = v;
+    } else if (col0 + c < d) {
+      A[(long)i * d + col0 + c] = -v;
     }
+  });
 }
 
 // U (fp32) <- upper triangle of A, zeros below.

@@ -434,16 +434,16 @@ __global__ __launch_bounds__(256) void commit_group_kernel(
 
 // W'[:, c_begin:c_end] -= Et^T * U[k0:k0+Kd, c_begin:c_end]   (Eq. 4 applied to a whole block:
 // the lazy update of the columns not yet quantized; also the rest-of-block update when g < B)
-__global__ __launch_bounds__(kGemmThreads) void tail_update_kernel(
+__global__ __launch_bounds__(TailGemm::kThreads) void tail_update_kernel(
     const float* __restrict__ Et, int lde, int Kd, const float* __restrict__ U, int ldu, int k0,
     float* __restrict__ Wp, int ldw, int d_out, int c_begin, int c_end, int tiles_n) {
   const int tm = blockIdx.x / tiles_n, tn = blockIdx.x % tiles_n;
-  TileAcc acc;
-  zero_acc(acc);
-  mfma_kmajor_tile<false>(Et, lde, tm * kTileM, lde, U + (long)k0 * ldu, ldu,
-                          c_begin + tn * kTileN, c_end, 0, Kd, acc);
-  const int r0 = tm * kTileM, c0 = c_begin + tn * kTileN;
-  for_each_acc(acc, [&](int row, int col, float v) {
+  TailGemm::Acc acc;
+  TailGemm::zero(acc);
+  TailGemm::run<false>(Et, lde, tm * TailGemm::kTileM, lde, U + (long)k0 * ldu, ldu,
+                       c_begin + tn * TailGemm::kTileN, c_end, 0, Kd, acc);
+  const int r0 = tm * TailGemm::kTileM, c0 = c_begin + tn * TailGemm::kTileN;
+  TailGemm::for_each(acc, [&](int row, int col, float v) {
     const int r = r0 + row, c = c0 + col;
     if (r < d_out && c < c_end) Wp[(long)r * ldw + c] -= v;
   });
@@ -599,13 +599,14 @@ static int launch_tail_update(hipStream_t stream, const float* Et, int lde, int 
   static bool attr_set = false;
   if (!attr_set) {
     BPDQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(tail_update_kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmLdsBytes));
+                                     hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)TailGemm::kLdsBytes));
     attr_set = true;
   }
-  const int tiles_m = lde / kTileM + (lde % kTileM ? 1 : 0);
-  const int tiles_n = bpdq_ceil_div(c_end - c_begin, kTileN);
-  hipLaunchKernelGGL(tail_update_kernel, dim3(tiles_m * tiles_n), dim3(kGemmThreads), kGemmLdsBytes,
-                     stream, Et, lde, Kd, U, d_in, k0, Wp, d_in, d_out, c_begin, c_end, tiles_n);
+  const int tiles_m = bpdq_ceil_div(lde, TailGemm::kTileM);
+  const int tiles_n = bpdq_ceil_div(c_end - c_begin, TailGemm::kTileN);
+  hipLaunchKernelGGL(tail_update_kernel, dim3(tiles_m * tiles_n), dim3(TailGemm::kThreads),
+                     TailGemm::kLdsBytes, stream, Et, lde, Kd, U, d_in, k0, Wp, d_in, d_out, c_begin, c_end, tiles_n);
   BPDQ_LAUNCH_CHECK();
   return 0;
 }
