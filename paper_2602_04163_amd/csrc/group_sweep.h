@@ -1,0 +1,513 @@
+// Steps 3-4 of the pass: the group / column sweep of BPDQ with lazy block updates
+// (paper Sec. 3.2, 3.3; Eq. 3-9; App. B).
+//
+// Mapping.  Every formula of the method is row-wise; the only sequential axis is the column
+// index inside a group.  One row of a group lives in 16 lanes (one DPP row): column j sits in
+// lane j % 16, register slot j / 16, so the live columns stay spread over all 16 lanes while
+// the sweep advances.  A wavefront carries 4 rows, a work-group 16.  The local factor
+// U_loc (g x g) is staged once per work-group in LDS, permuted so that a lane's slots are
+// contiguous, with the diagonal and lower part zeroed (no masks in the inner loop).
+//
+// What is computed.  For a row with group-start working weights t and bit rows b_i, all the
+// quantities the method needs are right-solves with U_loc:
+//     tau = t U_loc^-1,   P_0 = 1 U_loc^-1,   P_i = b_i U_loc^-1.
+// They are produced by the same forward recurrence as the error propagation of Eq. 3-4
+// (x_l = v_l / U_ll;  v_{l+1:} -= x_l U_{l,l+1:}), so the bit-plane update of a column, its
+// error coordinate and the k plane solves advance together, one column per step.  Then
+//   * the fit of Eq. 6 is the (k+1) x (k+1) system G c = r with G_ab = P_a.P_b, r_a = P_a.tau
+//     (since U_loc^-T B_r = [P_0 .. P_k]^T), accumulated and solved in fp64;
+//   * the corrected propagation coordinates of Eq. 9 are E' = tau - sum_a c_a P_a
+//     (App. B.3: E' U_loc = T - What_new), so What_old / Delta E are never materialised;
+//   * the score of an iterate is ||E'||^2.
+// Decisions (8-bit RTN code, nearest level) are taken in fp32 in a fixed operation order.
+#pragma once
+#include <utility>
+
+#include "mfma_kmajor.h"
+
+namespace bpdq {
+
+constexpr int kRowsPerWG = 16;
+constexpr int kSweepThreads = 256;
+
+// ------------------------------------------------------------------ lane helpers -----------
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float x) {
+  return __builtin_bit_cast(
+      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, false));
+}
+template <int CTRL>
+__device__ __forceinline__ double dpp_d(double x) {
+  const long long b = __builtin_bit_cast(long long, x);
+  const int lo = __builtin_amdgcn_update_dpp(0, (int)(b & 0xffffffffLL), CTRL, 0xF, 0xF, false);
+  const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), CTRL, 0xF, 0xF, false);
+  return __builtin_bit_cast(double, ((long long)hi << 32) | (unsigned int)lo);
+}
+// value of lane O of this 16-lane row, in every lane of the row
+template <int O>
+__device__ __forceinline__ float bcast16(float x) { return dpp_f<0x150 + O>(x); }
+
+// Butterfly over the 16 lanes of a row: xor 1, xor 2 (quad permutes), then half-row mirror and
+// row mirror, which act as xor 4 / xor 8 once quads are uniform.  Every lane ends with the same
+// bits (each stage adds the same two operands in both partners).
+template <typename OP>
+__device__ __forceinline__ float row_reduce_f(float v, OP op) {
+  v = op(v, dpp_f<0xB1>(v));
+  v = op(v, dpp_f<0x4E>(v));
+  v = op(v, dpp_f<0x141>(v));
+  v = op(v, dpp_f<0x140>(v));
+  return v;
+}
+__device__ __forceinline__ double row_sum_d(double v) {
+  v += dpp_d<0xB1>(v);
+  v += dpp_d<0x4E>(v);
+  v += dpp_d<0x141>(v);
+  v += dpp_d<0x140>(v);
+  return v;
+}
+
+// ------------------------------------------------------------------ per-row state ----------
+template <int K, int G>
+struct RowState {
+  static constexpr int CPL = G / 16;
+  float t[CPL];       // group-start working weights (frozen for the group)
+  float tau[CPL];     // t U_loc^-1
+  float p0[CPL];      // 1 U_loc^-1
+  float wg[CPL];      // working copy during a sweep
+  float P[K][CPL];    // running right-hand sides, then P_i = b_i U_loc^-1
+  int code[CPL];      // plane bits of my columns, bit (i-1) = B_i
+};
+
+// One column of the forward recurrence.  SWEEP = false: initial pass (codes known, also
+// builds tau and P_0).  SWEEP = true: bit-plane update of column L (Eq. 7-8), its error
+// coordinate (Eq. 3) and compensation of the later columns (Eq. 4), plus the plane solves.
+template <int K, int G, int L, bool SWEEP>
+__device__ __forceinline__ void column_step(RowState<K, G>& st, const float* __restrict__ sU,
+                                            const float* __restrict__ sInv,
+                                            const float (&lv)[1 << K], int lane16) {
+  constexpr int CPL = G / 16, M = L / 16, O = L % 16;
+  const float inv = sInv[L];
+  const bool owner = (lane16 == O);
+  float u[CPL];
+#pragma unroll
+  for (int m = M; m < CPL; ++m) u[m] = sU[L * G + lane16 * CPL + m];
+
+  float x[K], xb[K];
+  if constexpr (SWEEP) {
+    const float w = st.wg[M];
+    float diff = w - lv[0];
+    float bd = diff * diff;
+    float bq = lv[0];
+    int bc = 0;
+#pragma unroll
+    for (int c = 1; c < (1 << K); ++c) {
+      diff = w - lv[c];
+      const float dist = diff * diff;
+      const bool lt = dist < bd;      // strict: the lowest code wins ties
+      bd = lt ? dist : bd;
+      bq = lt ? lv[c] : bq;
+      bc = lt ? c : bc;
+    }
+    const float e = (w - bq) * inv;
+#pragma unroll
+    for (int i = 0; i < K; ++i) x[i] = ((float)((bc >> i) & 1) + st.P[i][M]) * inv;
+    if (owner) st.code[M] = bc;
+    const float eb = bcast16<O>(e);
+#pragma unroll
+    for (int m = M; m < CPL; ++m) st.wg[m] = fmaf(-eb, u[m], st.wg[m]);
+  } else {
+    const float xt = st.tau[M] * inv;
+    const float x0 = st.p0[M] * inv;
+#pragma unroll
+    for (int i = 0; i < K; ++i) x[i] = ((float)((st.code[M] >> i) & 1) + st.P[i][M]) * inv;
+    if (owner) {
+      st.tau[M] = xt;
+      st.p0[M] = x0;
+    }
+    const float tb = bcast16<O>(xt);
+    const float ob = bcast16<O>(x0);
+#pragma unroll
+    for (int m = M; m < CPL; ++m) {
+      st.tau[m] = fmaf(-tb, u[m], st.tau[m]);
+      st.p0[m] = fmaf(-ob, u[m], st.p0[m]);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < K; ++i) {
+    if (owner) st.P[i][M] = x[i];
+    xb[i] = bcast16<O>(x[i]);
+#pragma unroll
+    for (int m = M; m < CPL; ++m) st.P[i][m] = fmaf(-xb[i], u[m], st.P[i][m]);
+  }
+}
+
+template <int K, int G, bool SWEEP, int... Ls>
+__device__ __forceinline__ void run_columns(RowState<K, G>& st, const float* sU, const float* sInv,
+                                            const float (&lv)[1 << K], int lane16,
+                                            std::integer_sequence<int, Ls...>) {
+  (column_step<K, G, Ls, SWEEP>(st, sU, sInv, lv, lane16), ...);
+}
+
+// Coefficient fit (Eq. 6) from the solved vectors; returns c (fp32) and the row's ||E'||^2.
+template <int K, int G>
+__device__ __forceinline__ double fit_and_score(const RowState<K, G>& st, double alpha,
+                                                float (&c32)[K + 1], float (&Ep)[G / 16]) {
+  constexpr int CPL = G / 16, N = K + 1;
+  double Gm[N][N], r[N];
+#pragma unroll
+  for (int a = 0; a < N; ++a) {
+#pragma unroll
+    for (int b = a; b < N; ++b) {
+      double s = 0.0;
+#pragma unroll
+      for (int m = 0; m < CPL; ++m) {
+        const float va = (a == 0) ? st.p0[m] : st.P[a - 1 < 0 ? 0 : a - 1][m];
+        const float vb = (b == 0) ? st.p0[m] : st.P[b - 1 < 0 ? 0 : b - 1][m];
+        s += (double)va * (double)vb;
+      }
+      Gm[a][b] = row_sum_d(s);
+    }
+    double s = 0.0;
+#pragma unroll
+    for (int m = 0; m < CPL; ++m) {
+      const float va = (a == 0) ? st.p0[m] : st.P[a - 1 < 0 ? 0 : a - 1][m];
+      s += (double)va * (double)st.tau[m];
+    }
+    r[a] = row_sum_d(s);
+  }
+  double tr = 0.0;
+#pragma unroll
+  for (int a = 0; a < N; ++a) tr += Gm[a][a];
+  const double mu = alpha * tr / (double)N;
+#pragma unroll
+  for (int a = 0; a < N; ++a) {
+    Gm[a][a] += mu;
+#pragma unroll
+    for (int b = 0; b < a; ++b) Gm[a][b] = Gm[b][a];
+  }
+  // Gaussian elimination without pivoting (G is symmetric positive definite after the ridge)
+#pragma unroll
+  for (int p = 0; p < N; ++p) {
+    const double ip = 1.0 / Gm[p][p];
+#pragma unroll
+    for (int a = p + 1; a < N; ++a) {
+      const double f = Gm[a][p] * ip;
+#pragma unroll
+      for (int b = p + 1; b < N; ++b) Gm[a][b] -= f * Gm[p][b];
+      r[a] -= f * r[p];
+    }
+  }
+  double c[N];
+#pragma unroll
+  for (int a = N - 1; a >= 0; --a) {
+    double s = r[a];
+#pragma unroll
+    for (int b = a + 1; b < N; ++b) s -= Gm[a][b] * c[b];
+    c[a] = s / Gm[a][a];
+  }
+#pragma unroll
+  for (int a = 0; a < N; ++a) c32[a] = (float)c[a];
+  double sc = 0.0;
+#pragma unroll
+  for (int m = 0; m < CPL; ++m) {
+    float e = fmaf(-c32[0], st.p0[m], st.tau[m]);
+#pragma unroll
+    for (int i = 0; i < K; ++i) e = fmaf(-c32[i + 1], st.P[i][m], e);
+    Ep[m] = e;
+    sc += (double)e * (double)e;
+  }
+  return row_sum_d(sc);
+}
+
+// v(code) = ((c0 + b1 c1) + b2 c2) + ...  in fp32 (Eq. 7)
+template <int K>
+__device__ __forceinline__ void level_table(const float (&c)[K + 1], float (&lv)[1 << K]) {
+#pragma unroll
+  for (int code = 0; code < (1 << K); ++code) {
+    float v = c[0];
+#pragma unroll
+    for (int i = 0; i < K; ++i)
+      if ((code >> i) & 1) v = v + c[i + 1];
+    lv[code] = v;
+  }
+}
+
+template <int K, int G>
+struct Candidates {          // per-iterate scratch in the workspace
+  unsigned char* codes;      // [T+1][d_out][G]
+  float* coef;               // [T+1][d_out][K+1]
+  float* E;                  // [T+1][d_out][G]
+  double* score;             // [T+1][n_wg]
+};
+
+template <int K, int G>
+__device__ __forceinline__ void store_candidate(const RowState<K, G>& st, const float (&c32)[K + 1],
+                                                const float (&Ep)[G / 16], double rowscore, int it,
+                                                int row, bool valid, int d_out, int n_wg,
+                                                unsigned char* codes, float* coef, float* E,
+                                                double* score, double* sScore, int lane16) {
+  constexpr int CPL = G / 16;
+  if (valid) {
+    const long base = ((long)it * d_out + row) * G;
+#pragma unroll
+    for (int m = 0; m < CPL; ++m) {
+      codes[base + 16 * m + lane16] = (unsigned char)st.code[m];
+      E[base + 16 * m + lane16] = Ep[m];
+    }
+    if (lane16 <= K) {
+      float v = c32[0];
+#pragma unroll
+      for (int i = 1; i <= K; ++i) v = (lane16 == i) ? c32[i] : v;
+      coef[((long)it * d_out + row) * (K + 1) + lane16] = v;
+    }
+  }
+  __syncthreads();
+  if (lane16 == 0) sScore[threadIdx.x >> 4] = valid ? rowscore : 0.0;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double s = 0.0;
+    for (int q = 0; q < kRowsPerWG; ++q) s += sScore[q];
+    score[(long)it * n_wg + blockIdx.x] = s;
+  }
+}
+
+// One group of g columns for 16 rows per work-group: initialisation, fit, T refinement
+// iterations; every iterate's (codes, coefficients, E', score) is kept for the selection.
+template <int K, int G>
+__global__ __launch_bounds__(kSweepThreads) void bpdq_group_kernel(
+    const float* __restrict__ Wp, int ldw, int d_out, const float* __restrict__ U, int ldu, int s0,
+    int T, float alpha, unsigned char* __restrict__ cand_codes, float* __restrict__ cand_coef,
+    float* __restrict__ cand_E, double* __restrict__ cand_score) {
+  constexpr int CPL = G / 16;
+  extern __shared__ float lds[];
+  float* sU = lds;                 // [G][16][CPL], zero on and below the diagonal
+  float* sInv = lds + G * G;       // 1 / U_ll
+  double* sScore = reinterpret_cast<double*>(lds + G * G + G);
+  const int tid = threadIdx.x;
+  const int lane16 = tid & 15;
+  for (int e = tid; e < G * G; e += kSweepThreads) {
+    const int l = e / G, j = e % G;
+    const float v = U[(long)(s0 + l) * ldu + s0 + j];
+    sU[l * G + (j & 15) * CPL + (j >> 4)] = (j > l) ? v : 0.f;
+    if (j == l) sInv[l] = 1.0f / v;
+  }
+  __syncthreads();
+
+  const int row = blockIdx.x * kRowsPerWG + (tid >> 4);
+  const bool valid = row < d_out;
+  const int rr = valid ? row : d_out - 1;
+  RowState<K, G> st;
+  const float* wrow = Wp + (long)rr * ldw + s0;
+#pragma unroll
+  for (int m = 0; m < CPL; ++m) st.t[m] = wrow[16 * m + lane16];
+
+  // ---- bit-plane initialisation (Sec. 3.2, Eq. 5): 8-bit affine RTN, keep the k MSB planes
+  float lo = st.t[0], hi = st.t[0];
+#pragma unroll
+  for (int m = 1; m < CPL; ++m) {
+    lo = fminf(lo, st.t[m]);
+    hi = fmaxf(hi, st.t[m]);
+  }
+  lo = row_reduce_f(lo, [](float a, float b) { return fminf(a, b); });
+  hi = row_reduce_f(hi, [](float a, float b) { return fmaxf(a, b); });
+  const float sc = (hi - lo) / 255.0f;
+  const bool flat = (hi == lo);
+#pragma unroll
+  for (int m = 0; m < CPL; ++m) {
+    const float q = (st.t[m] - lo) / (flat ? 1.0f : sc);
+    float z = rintf(q);                       // round half to even
+    z = fminf(fmaxf(z, 0.f), 255.f);
+    st.code[m] = flat ? 0 : ((int)z >> (8 - K));
+    st.tau[m] = st.t[m];
+    st.p0[m] = 1.0f;
+#pragma unroll
+    for (int i = 0; i < K; ++i) st.P[i][m] = 0.f;
+  }
+  float lv[1 << K];
+#pragma unroll
+  for (int c = 0; c < (1 << K); ++c) lv[c] = 0.f;
+  using Seq = std::make_integer_sequence<int, G>;
+  run_columns<K, G, false>(st, sU, sInv, lv, lane16, Seq{});
+
+  const int n_wg = gridDim.x;
+  float c32[K + 1], Ep[CPL];
+  double rs = fit_and_score<K, G>(st, (double)alpha, c32, Ep);
+  store_candidate<K, G>(st, c32, Ep, rs, 0, row, valid, d_out, n_wg, cand_codes, cand_coef,
+                        cand_E, cand_score, sScore, lane16);
+
+  // ---- refinement iterations (Sec. 3.3)
+  for (int it = 1; it <= T; ++it) {
+    level_table<K>(c32, lv);
+#pragma unroll
+    for (int m = 0; m < CPL; ++m) {
+      st.wg[m] = st.t[m];
+#pragma unroll
+      for (int i = 0; i < K; ++i) st.P[i][m] = 0.f;
+    }
+    run_columns<K, G, true>(st, sU, sInv, lv, lane16, Seq{});
+    rs = fit_and_score<K, G>(st, (double)alpha, c32, Ep);
+    store_candidate<K, G>(st, c32, Ep, rs, it, row, valid, d_out, n_wg, cand_codes, cand_coef,
+                          cand_E, cand_score, sScore, lane16);
+  }
+}
+
+// Selection + commit of one group, 16 rows per work-group (same lane mapping as the sweep).
+// Every work-group first sums the row-block scores of each iterate in one fixed order and takes
+// the earliest minimum (Sec. 3.3: keep the iterate with the smallest ||E_group||_F^2), so all
+// work-groups agree bit for bit; work-group 0 publishes grp_iter / grp_err.  Then the kept
+// iterate is written out: packed planes (wave ballots), coefficients, What, and E* transposed
+// into the block's K-major error buffer Eblk[(s0 - b0) + j][row] (leading dimension lde).
+template <int K, int G>
+__global__ __launch_bounds__(256) void commit_group_kernel(
+    const unsigned char* __restrict__ cand_codes, const float* __restrict__ cand_coef,
+    const float* __restrict__ cand_E, const double* __restrict__ cand_score, int n_wg, int T,
+    double* __restrict__ grp_err, int* __restrict__ grp_iter, int d_out, int d_in, int s0, int b0,
+    uint32_t* __restrict__ planes, float* __restrict__ coefs, float* __restrict__ W_hat,
+    float* __restrict__ Eblk, int lde) {
+  constexpr int CPL = G / 16;
+  __shared__ double tot[64];
+  __shared__ float sE[G][17];
+  const int tid = threadIdx.x, lane16 = tid & 15;
+  // iterate q is summed by wavefront q % 4: strided partial sums per lane, then a fixed
+  // xor butterfly over the 64 lanes
+  for (int q = tid >> 6; q <= T; q += 4) {
+    double s = 0.0;
+    for (int w = tid & 63; w < n_wg; w += 64) s += cand_score[(long)q * n_wg + w];
+#pragma unroll
+    for (int m = 32; m > 0; m >>= 1) s += __shfl_xor(s, m, 64);
+    if ((tid & 63) == 0) tot[q] = s;
+  }
+  __syncthreads();
+  int it = 0;
+  for (int q = 1; q <= T; ++q)
+    if (tot[q] < tot[it]) it = q;
+  if (blockIdx.x == 0 && tid == 0) {
+    *grp_iter = it;
+    *grp_err = tot[it];
+  }
+
+  const int row0 = blockIdx.x * kRowsPerWG;
+  const int rloc = tid >> 4;
+  const int row = row0 + rloc;
+  const bool valid = row < d_out;
+  const int rr = valid ? row : d_out - 1;
+  const int n_grp = d_in / G, gi = s0 / G, n_word = d_in / 32;
+  const long cbase = ((long)it * d_out + rr) * G;
+  float c[K + 1], lv[1 << K];
+#pragma unroll
+  for (int i = 0; i <= K; ++i) c[i] = cand_coef[((long)it * d_out + rr) * (K + 1) + i];
+  level_table<K>(c, lv);
+  int code[CPL];
+#pragma unroll
+  for (int m = 0; m < CPL; ++m) {
+    code[m] = cand_codes[cbase + 16 * m + lane16];
+    sE[16 * m + lane16][rloc] = valid ? cand_E[cbase + 16 * m + lane16] : 0.f;
+  }
+  // planes: a wave ballot holds bit (16 q + lane16) for row q of the wave
+  const int shift = 16 * ((tid & 63) >> 4);
+#pragma unroll
+  for (int i = 0; i < K; ++i) {
+#pragma unroll
+    for (int w = 0; w < G / 32; ++w) {
+      const unsigned long long lo = __ballot((code[2 * w] >> i) & 1);
+      const unsigned long long hi = __ballot((code[2 * w + 1] >> i) & 1);
+      const uint32_t word = (uint32_t)((lo >> shift) & 0xffffu) | ((uint32_t)((hi >> shift) & 0xffffu) << 16);
+      if (valid && lane16 == 0) planes[((long)i * d_out + row) * n_word + s0 / 32 + w] = word;
+    }
+  }
+  if (valid) {
+    if (W_hat) {
+#pragma unroll
+      for (int m = 0; m < CPL; ++m) {
+        float v = lv[0];
+#pragma unroll
+        for (int q = 1; q < (1 << K); ++q) v = (code[m] == q) ? lv[q] : v;
+        W_hat[(long)row * d_in + s0 + 16 * m + lane16] = v;
+      }
+    }
+    if (lane16 <= K) {
+      float v = c[0];
+#pragma unroll
+      for (int i = 1; i <= K; ++i) v = (lane16 == i) ? c[i] : v;
+      coefs[((long)lane16 * d_out + row) * n_grp + gi] = v;
+    }
+  }
+  __syncthreads();
+  for (int idx = tid; idx < G * kRowsPerWG; idx += 256) {
+    const int j = idx >> 4, r = idx & 15;
+    Eblk[(long)(s0 - b0 + j) * lde + row0 + r] = sE[j][r];
+  }
+}
+
+// ------------------------------------------------------------------ host side --------------
+struct QuantLayout {
+  size_t wp_off, eblk_off, codes_off, coef_off, e_off, score_off, total;
+  int B, lde, n_wg;
+};
+
+static inline QuantLayout quant_layout(int d_out, int d_in, const bpdq_params& p) {
+  QuantLayout L;
+  const int g = p.group, T = p.refine_iters, K = p.bits;
+  L.B = p.block > g ? p.block : g;
+  L.lde = (int)bpdq_align_up((size_t)d_out, 64);
+  L.n_wg = bpdq_ceil_div(d_out, kRowsPerWG);
+  size_t off = 0;
+  L.wp_off = off;    off += bpdq_align_up((size_t)d_out * d_in * sizeof(float), 256);
+  L.eblk_off = off;  off += bpdq_align_up((size_t)L.B * L.lde * sizeof(float), 256);
+  L.codes_off = off; off += bpdq_align_up((size_t)(T + 1) * d_out * g, 256);
+  L.coef_off = off;  off += bpdq_align_up((size_t)(T + 1) * d_out * (K + 1) * sizeof(float), 256);
+  L.e_off = off;     off += bpdq_align_up((size_t)(T + 1) * d_out * g * sizeof(float), 256);
+  L.score_off = off; off += bpdq_align_up((size_t)(T + 1) * L.n_wg * sizeof(double), 256);
+  L.total = off;
+  return L;
+}
+
+template <int K, int G>
+static inline int launch_group(hipStream_t stream, const float* Wp, int d_out, int d_in, const float* U,
+                        int s0, int b0, const bpdq_params& p, const QuantLayout& L, char* base,
+                        uint32_t* planes, float* coefs, float* W_hat, double* grp_err,
+                        int* grp_iter) {
+  unsigned char* c_codes = reinterpret_cast<unsigned char*>(base + L.codes_off);
+  float* c_coef = reinterpret_cast<float*>(base + L.coef_off);
+  float* c_E = reinterpret_cast<float*>(base + L.e_off);
+  double* c_score = reinterpret_cast<double*>(base + L.score_off);
+  float* Eblk = reinterpret_cast<float*>(base + L.eblk_off);
+  const size_t lds = (size_t)(G * G + G) * sizeof(float) + kRowsPerWG * sizeof(double);
+  static bool attr_set = false;
+  if (!attr_set) {
+    BPDQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(bpdq_group_kernel<K, G>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    attr_set = true;
+  }
+  const int gi = s0 / G;
+  hipLaunchKernelGGL((bpdq_group_kernel<K, G>), dim3(L.n_wg), dim3(kSweepThreads), lds, stream, Wp,
+                     d_in, d_out, U, d_in, s0, p.refine_iters, p.alpha, c_codes, c_coef, c_E, c_score);
+  BPDQ_LAUNCH_CHECK();
+  hipLaunchKernelGGL((commit_group_kernel<K, G>), dim3(L.lde / kRowsPerWG), dim3(256), 0, stream,
+                     c_codes, c_coef, c_E, c_score, L.n_wg, p.refine_iters, grp_err + gi,
+                     grp_iter + gi, d_out, d_in, s0, b0, planes, coefs, W_hat, Eblk, L.lde);
+  BPDQ_LAUNCH_CHECK();
+  return 0;
+}
+
+typedef int (*GroupLauncher)(hipStream_t, const float*, int, int, const float*, int, int,
+                             const bpdq_params&, const QuantLayout&, char*, uint32_t*, float*,
+                             float*, double*, int*);
+
+// One translation unit per plane count instantiates the group kernels (they are large, fully
+// unrolled kernels; splitting them keeps the build parallel).
+GroupLauncher pick_group_k1(int g);
+GroupLauncher pick_group_k2(int g);
+GroupLauncher pick_group_k3(int g);
+GroupLauncher pick_group_k4(int g);
+
+template <int K>
+static inline GroupLauncher pick_group_g(int g) {
+  switch (g) {
+    case 32: return launch_group<K, 32>;
+    case 64: return launch_group<K, 64>;
+    case 128: return launch_group<K, 128>;
+  }
+  return nullptr;
+}
+}  // namespace bpdq

@@ -1,99 +1,170 @@
 // Step 1 of the pass: calibration Hessian H += scale * Xc^T Xc (paper Sec. 3.1, H = X X^T).
 //
 // A symmetric rank-k update on the fp32 matrix cores.  Only the upper triangle of 256 x 256
-// tiles is computed.  The token axis is cut into S deterministic slices so that
-// (tiles x S) work-groups fill the 256 compute units; slice partials go to the workspace and
-// are summed in a fixed order (no float atomics => bit-reproducible H).
+// tiles is computed, and of a diagonal tile only the 32 x 32 blocks on or above the diagonal.
+// The token axis is cut into deterministic slices so that the work-groups fill the 256 compute
+// units in whole rounds: off-diagonal tiles into S_off slices, diagonal tiles (5/8 of the work
+// per token) into fewer, longer slices S_diag, so that every work-group costs about the same.
+// Slice partials go to the workspace and are summed in a fixed order (no float atomics, so H is
+// bit-reproducible).
 #include "mfma_kmajor.h"
 
 namespace bpdq {
 
-constexpr int kNumCU = 256;   // MI355X
+constexpr int kNumCU = 256;   // MI355X: 8 XCDs x 32 compute units
+constexpr int kNumXCD = 8;
+constexpr int kTileFloats = HessGemm::kTileM * HessGemm::kTileN;
 
 struct HessPlan {
-  int nb;        // tile rows/cols
-  int n_tiles;   // upper-triangular tiles
-  int S;         // token slices
-  int k_per;     // tokens per slice (multiple of kStageK)
+  int nb;               // tile rows / cols
+  int n_off, n_diag;    // off-diagonal and diagonal tiles of the upper triangle
+  int S_off, S_diag;    // token slices per off-diagonal / diagonal tile
+  int k_off, k_diag;    // tokens per slice (multiples of the stage depth)
+  bool direct;          // one slice each: accumulate into H without partials
+  int items() const { return n_off * S_off + n_diag * S_diag; }
+  size_t ws_bytes() const { return direct ? 0 : (size_t)items() * kTileFloats * sizeof(float); }
 };
 
+// Makespan (us) of the busiest XCD: work-groups go round-robin to the XCDs and, inside one, to
+// the first free of its 32 compute units; all off-diagonal slices are dispatched first.
+static double hess_makespan(int n_full, double c_full, int n_short, double c_short) {
+  const int per = kNumCU / kNumXCD;
+  const int nf = bpdq_ceil_div(n_full, kNumXCD), ns = bpdq_ceil_div(n_short, kNumXCD);
+  double free_at[kNumCU / kNumXCD];
+  const int q = nf / per, r = nf % per;
+  for (int i = 0; i < per; ++i) free_at[i] = (q + (i < r ? 1 : 0)) * c_full;
+  for (int j = 0; j < ns; ++j) {
+    int m = 0;
+    for (int i = 1; i < per; ++i)
+      if (free_at[i] < free_at[m]) m = i;
+    free_at[m] += c_short;
+  }
+  double t = 0.0;
+  for (int i = 0; i < per; ++i) t = free_at[i] > t ? free_at[i] : t;
+  return t;
+}
+
 static HessPlan plan_hessian(int n_tok, int d_in) {
+  static HessPlan cache;
+  static int cache_n = -1, cache_d = -1;
+  if (n_tok == cache_n && d_in == cache_d) return cache;
   HessPlan p;
   p.nb = bpdq_ceil_div(d_in, HessGemm::kTileM);
-  p.n_tiles = p.nb * (p.nb + 1) / 2;
-  p.S = 1;
-  p.k_per = (int)bpdq_align_up((size_t)(n_tok > 0 ? n_tok : 1), kStageK);
-  if (n_tok <= 0 || p.n_tiles >= 4 * kNumCU) return p;
-  // estimated time (us) = rounds * (slice MFMA time + fixed cost) + reduction traffic
-  const double us_per_tok = 0.28, us_fixed = 8.0, us_per_partial = 0.131;
-  double best = 1e300;
-  const int s_max = n_tok / 256 < 64 ? (n_tok / 256 < 1 ? 1 : n_tok / 256) : 64;
-  for (int S = 1; S <= s_max; ++S) {
-    const int k_per = (int)bpdq_align_up((size_t)bpdq_ceil_div(n_tok, S), kStageK);
-    const int rounds = bpdq_ceil_div(p.n_tiles * S, kNumCU);
-    double t = rounds * (k_per * us_per_tok + us_fixed);
-    if (S > 1) t += (double)p.n_tiles * S * us_per_partial;
-    if (t < best * 0.995) {
-      best = t;
-      p.S = S;
-      p.k_per = k_per;
+  p.n_diag = p.nb;
+  p.n_off = p.nb * (p.nb - 1) / 2;
+  p.S_off = p.S_diag = 1;
+  p.k_off = p.k_diag = (int)bpdq_align_up((size_t)(n_tok > 0 ? n_tok : 1), HessGemm::kStageK);
+  p.direct = true;
+  if (n_tok > 0 && p.n_off + p.n_diag < 4 * kNumCU) {
+    // per-token MFMA time of one 256 x 256 tile, fixed cost per work-group, cost per partial tile
+    const double us_per_tok = 0.26, us_fixed = 8.0, us_per_partial = 0.131, diag_frac = 0.64;
+    const int s_max = n_tok / 256 < 64 ? (n_tok / 256 < 1 ? 1 : n_tok / 256) : 64;
+    double best = 1e300;
+    for (int So = 1; So <= s_max; ++So) {
+      for (int dd = -1; dd <= 1; ++dd) {
+        int Sd = (int)(So * 0.625 + 0.5) + dd;
+        if (Sd < 1) Sd = 1;
+        if (Sd > s_max) Sd = s_max;
+        const int ko = (int)bpdq_align_up((size_t)bpdq_ceil_div(n_tok, So), HessGemm::kStageK);
+        const int kd = (int)bpdq_align_up((size_t)bpdq_ceil_div(n_tok, Sd), HessGemm::kStageK);
+        double t = hess_makespan(p.n_off * So, ko * us_per_tok + us_fixed, p.n_diag * Sd,
+                                 kd * us_per_tok * diag_frac + us_fixed);
+        if (So > 1 || Sd > 1) t += (double)(p.n_off * So + p.n_diag * Sd) * us_per_partial;
+        if (t < best * 0.998) {
+          best = t;
+          p.S_off = So; p.S_diag = Sd; p.k_off = ko; p.k_diag = kd;
+        }
+      }
     }
+    p.direct = (p.S_off == 1 && p.S_diag == 1);
   }
+  cache = p; cache_n = n_tok; cache_d = d_in;
   return p;
 }
 
-__device__ __forceinline__ void decode_upper_tile(int tile, int nb, int& bi, int& bj) {
+// off-diagonal tile index (row-major over bi < bj) -> (bi, bj)
+__device__ __forceinline__ void decode_off_tile(int tile, int nb, int& bi, int& bj) {
   bi = 0;
-  while (tile >= nb - bi) {
-    tile -= nb - bi;
+  while (tile >= nb - 1 - bi) {
+    tile -= nb - 1 - bi;
     ++bi;
   }
-  bj = bi + tile;
+  bj = bi + 1 + tile;
 }
 
 __global__ __launch_bounds__(HessGemm::kThreads) void hess_syrk_f32_kernel(
     const float* __restrict__ X, int n_tok, int d, long ldx, float scale, float* __restrict__ H,
-    float* __restrict__ partial, int nb, int n_tiles, int S, int k_per) {
+    float* __restrict__ partial, HessPlan p) {
   const int item = blockIdx.x;
-  const int split = item / n_tiles;
-  int bi, bj;
-  decode_upper_tile(item % n_tiles, nb, bi, bj);
-  const int k_begin = split * k_per;
-  const int k_end = min(n_tok, k_begin + k_per);
+  const int n_off_items = p.n_off * p.S_off;
+  int bi, bj, k_begin, k_end;
+  if (item < n_off_items) {
+    decode_off_tile(item % p.n_off, p.nb, bi, bj);
+    k_begin = (item / p.n_off) * p.k_off;
+    k_end = min(n_tok, k_begin + p.k_off);
+  } else {
+    const int j = item - n_off_items;
+    bi = bj = j % p.n_diag;
+    k_begin = (j / p.n_diag) * p.k_diag;
+    k_end = min(n_tok, k_begin + p.k_diag);
+  }
   HessGemm::Acc acc;
   HessGemm::zero(acc);
-  if (bi == bj) {
-    HessGemm::run<true>(X, ldx, bi * HessGemm::kTileM, d, X, ldx, bj * HessGemm::kTileN, d, k_begin, k_end, acc);
-  } else {
-    HessGemm::run<false>(X, ldx, bi * HessGemm::kTileM, d, X, ldx, bj * HessGemm::kTileN, d, k_begin, k_end, acc);
-  }
-  if (S == 1) {
-    const int r0 = bi * HessGemm::kTileM, c0 = bj * HessGemm::kTileN;
-    HessGemm::for_each(acc, [&](int row, int col, float v) {
+  const int r0 = bi * HessGemm::kTileM, c0 = bj * HessGemm::kTileN;
+  if (p.direct) {
+    auto emit = [&](int row, int col, float v) {
       const int r = r0 + row, c = c0 + col;
       if (r < d && c < d) H[(long)r * d + c] += scale * v;
-    });
+    };
+    if (bi == bj) {
+      HessGemm::run<2>(X, ldx, r0, d, X, ldx, c0, d, k_begin, k_end, acc);
+      HessGemm::for_each_diag(acc, emit);
+    } else {
+      HessGemm::run<0>(X, ldx, r0, d, X, ldx, c0, d, k_begin, k_end, acc);
+      HessGemm::for_each(acc, emit);
+    }
   } else {
-    float* out = partial + (long)item * (HessGemm::kTileM * HessGemm::kTileN);
-    HessGemm::for_each(acc, [&](int row, int col, float v) { out[row * HessGemm::kTileN + col] = v; });
+    float* out = partial + (long)item * kTileFloats;
+    auto emit = [&](int row, int col, float v) { out[row * HessGemm::kTileN + col] = v; };
+    if (bi == bj) {
+      // diagonal tile: only the 32 x 32 blocks on or above the diagonal are computed
+      HessGemm::run<2>(X, ldx, r0, d, X, ldx, c0, d, k_begin, k_end, acc);
+      HessGemm::for_each_diag(acc, emit);
+    } else {
+      HessGemm::run<0>(X, ldx, r0, d, X, ldx, c0, d, k_begin, k_end, acc);
+      HessGemm::for_each(acc, emit);
+    }
   }
 }
 
-// H[tile] += scale * sum_s partial[s][tile], slices added in index order.
+// H[tile] += scale * sum_s partial[s][tile], slices added in index order.  64 work-groups per
+// tile; tiles 0 .. n_off-1 are off-diagonal, the rest diagonal.
 __global__ __launch_bounds__(256) void hess_reduce_kernel(const float* __restrict__ partial,
-                                                          int n_tiles, int S, int nb, int d,
-                                                          float scale, float* __restrict__ H) {
+                                                          HessPlan p, int d, float scale,
+                                                          float* __restrict__ H) {
   const int tile = blockIdx.x >> 6;
   const int e = ((blockIdx.x & 63) * 256 + threadIdx.x) * 4;
-  int bi, bj;
-  decode_upper_tile(tile, nb, bi, bj);
+  int bi, bj, S;
+  long first, stride;
+  if (tile < p.n_off) {
+    decode_off_tile(tile, p.nb, bi, bj);
+    S = p.S_off;
+    first = tile;
+    stride = p.n_off;
+  } else {
+    bi = bj = tile - p.n_off;
+    S = p.S_diag;
+    first = (long)p.n_off * p.S_off + bi;
+    stride = p.n_diag;
+    // blocks of 32 x 32 below the diagonal of a diagonal tile are never computed
+    if ((e % HessGemm::kTileN) / 32 < (e / HessGemm::kTileN) / 32) return;
+  }
   const int r = bi * HessGemm::kTileM + e / HessGemm::kTileN;
   const int c = bj * HessGemm::kTileN + e % HessGemm::kTileN;
   if (r >= d || c >= d) return;
   float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
   for (int sp = 0; sp < S; ++sp) {
-    const float4 v = *reinterpret_cast<const float4*>(
-        partial + ((long)sp * n_tiles + tile) * (HessGemm::kTileM * HessGemm::kTileN) + e);
+    const float4 v = *reinterpret_cast<const float4*>(partial + (first + sp * stride) * kTileFloats + e);
     s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
   }
   float4* h = reinterpret_cast<float4*>(H + (long)r * d + c);
@@ -125,9 +196,7 @@ using namespace bpdq;
 
 extern "C" size_t bpdq_hessian_workspace_bytes(int n_tok, int d_in) {
   if (n_tok <= 0 || d_in <= 0) return 0;
-  const HessPlan p = plan_hessian(n_tok, d_in);
-  if (p.S == 1) return 0;
-  return (size_t)p.S * p.n_tiles * HessGemm::kTileM * HessGemm::kTileN * sizeof(float);
+  return plan_hessian(n_tok, d_in).ws_bytes();
 }
 
 extern "C" int bpdq_hessian_accumulate(const float* Xc, int n_tok, int d_in, int ldx, float scale,
@@ -141,7 +210,7 @@ extern "C" int bpdq_hessian_accumulate(const float* Xc, int n_tok, int d_in, int
   if (!H || (reinterpret_cast<uintptr_t>(H) & 15)) return -6;
   if (n_tok > 0) {
     const HessPlan p = plan_hessian(n_tok, d_in);
-    const size_t need = p.S == 1 ? 0 : (size_t)p.S * p.n_tiles * HessGemm::kTileM * HessGemm::kTileN * sizeof(float);
+    const size_t need = p.ws_bytes();
     if (need > 0 && (!ws || (reinterpret_cast<uintptr_t>(ws) & 15))) return -8;
     if (ws_bytes < need) return -9;
     static bool attr_set = false;
@@ -151,13 +220,13 @@ extern "C" int bpdq_hessian_accumulate(const float* Xc, int n_tok, int d_in, int
                                        (int)HessGemm::kLdsBytes));
       attr_set = true;
     }
-    hipLaunchKernelGGL(hess_syrk_f32_kernel, dim3(p.n_tiles * p.S), dim3(HessGemm::kThreads),
+    hipLaunchKernelGGL(hess_syrk_f32_kernel, dim3(p.items()), dim3(HessGemm::kThreads),
                        HessGemm::kLdsBytes, stream, Xc, n_tok, d_in, (long)ldx, scale, H,
-                       static_cast<float*>(ws), p.nb, p.n_tiles, p.S, p.k_per);
+                       static_cast<float*>(ws), p);
     BPDQ_LAUNCH_CHECK();
-    if (p.S > 1) {
-      hipLaunchKernelGGL(hess_reduce_kernel, dim3(p.n_tiles * 64), dim3(256), 0, stream,
-                         static_cast<const float*>(ws), p.n_tiles, p.S, p.nb, d_in, scale, H);
+    if (!p.direct) {
+      hipLaunchKernelGGL(hess_reduce_kernel, dim3((p.n_off + p.n_diag) * 64), dim3(256), 0, stream,
+                         static_cast<const float*>(ws), p, d_in, scale, H);
       BPDQ_LAUNCH_CHECK();
     }
   }
