@@ -256,7 +256,7 @@ def bpdq_group(T, UL, k, refine_iters, alpha=1e-4, select_per_row=False,
 # Steps 3-4 for a layer: groups in GPTQ order with lazy block updates
 # --------------------------------------------------------------------------- #
 def quantize_layer(W, U, dead, bits, group, block, refine_iters, alpha=1e-4,
-                   select_per_row=False, decision_dtype=np.float32, group_fn=None):
+                   select_per_row=False, decision_dtype=np.float32, group_fn=None, progress=None):
     """Sweep the columns of W block by block (Sec. 3.1 compensation; App. B.3 tail
     form).  Returns dict with
       code   uint8  (d_out x d_in)     plane bits, bit (i-1) = B_i
@@ -267,7 +267,8 @@ def quantize_layer(W, U, dead, bits, group, block, refine_iters, alpha=1e-4,
       grp_iter int32 (d_in/g) or (d_out, d_in/g) when select_per_row
       objective = sum grp_err  (= tr((W-What) Ht (W-What)^T), App. B.2)
     `group_fn(T, UL)` may replace the BPDQ group solver (used for the
-    fixed-uniform-grid comparison of App. A)."""
+    fixed-uniform-grid comparison of App. A).  `progress(b1, d_in)`, if given, is called after
+    every block (long runs report where they are)."""
     Wp = np.array(W, dtype=np.float64)
     U = np.asarray(U, dtype=np.float64)
     d_out, d_in = Wp.shape
@@ -309,6 +310,8 @@ def quantize_layer(W, U, dead, bits, group, block, refine_iters, alpha=1e-4,
             Wp[:, s + g:b1] -= res["E"] @ U[s:s + g, s + g:b1]
         # lazy block update of everything to the right
         Wp[:, b1:] -= Eall[:, b0:b1] @ U[b0:b1, b1:]
+        if progress is not None:
+            progress(b1, d_in)
     return dict(code=code, coef=coef, What=What, E=Eall, grp_err=grp_err, grp_iter=grp_iter,
                 objective=float(grp_err.sum()))
 

@@ -78,10 +78,12 @@ __device__ __forceinline__ double fast_rcp(double x) {
 //       one barrier, one reciprocal and a rank-1 update  a -= col col^T / pivot.
 //   (2) rows [64 b, 64 b + 64) of the panel above the block: X R^T = A12 solved by substitution,
 //       one thread per row, the row held in registers.
-// Work-group 0 also writes R into the diagonal block and reports a non-positive pivot.
+// Work-group 0 also writes R of the diagonal block to Rdiag (NB x NB, row-major, zero below the
+// diagonal, identity-padded) and reports a non-positive pivot.
 // Launch with max(p, 1) work-groups, p = number of 64-row blocks above the diagonal block.
 __global__ __launch_bounds__(256) void panel_factor_kernel(double* __restrict__ A, int d, int p0,
-                                                           int nb, int n_above, int* info) {
+                                                           int nb, int n_above,
+                                                           double* __restrict__ Rdiag, int* info) {
   __shared__ double sR[NB][NB + 1];     // R (upper) of the diagonal block
   __shared__ double sA[NB][NB + 1];     // panel tile of this work-group
   __shared__ double col[2][NB];
@@ -149,11 +151,10 @@ __global__ __launch_bounds__(256) void panel_factor_kernel(double* __restrict__ 
     sR[i][j] *= sInvD[j];
   }
   __syncthreads();
+  // R of the diagonal block goes to its own buffer: the block itself must stay untouched, because
+  // work-groups of this launch that start later still have to read it
   if (blockIdx.x == 0) {
-    for (int e = tid; e < NB * NB; e += 256) {
-      const int i = e / NB, j = e % NB;
-      if (i < nb && j < nb && j >= i) A[(long)(p0 + i) * d + p0 + j] = sR[i][j];
-    }
+    for (int e = tid; e < NB * NB; e += 256) Rdiag[e] = sR[e / NB][e % NB];
   }
   if (n_above == 0) return;
 
@@ -180,20 +181,19 @@ __global__ __launch_bounds__(256) void panel_factor_kernel(double* __restrict__ 
 }
 
 // Inverses of all diagonal blocks of R at once (one work-group per block, thread c solves
-// R x = e_c by back substitution).  Dinv[p] is NB x NB row-major, zero below the diagonal.
-__global__ __launch_bounds__(64) void diag_inverse_kernel(const double* __restrict__ A, int d,
-                                                          double* __restrict__ Dinv) {
+// R x = e_c by back substitution); the inverse replaces the diagonal block of A (upper part,
+// zeros below), which until now still held the unfactored block.
+__global__ __launch_bounds__(64) void diag_inverse_kernel(const double* __restrict__ Rdiag,
+                                                          double* __restrict__ A, int d) {
   __shared__ double s[NB][NB + 1];
   __shared__ double x[NB][NB + 1];
   const int p0 = blockIdx.x * NB;
   const int nb = (d - p0 < NB) ? d - p0 : NB;
   const int c = threadIdx.x;
+  const double* src = Rdiag + (long)blockIdx.x * NB * NB;
   for (int e = c; e < NB * NB; e += 64) {
-    const int i = e / NB, j = e % NB;
-    double v = (i == j) ? 1.0 : 0.0;
-    if (i < nb && j < nb && j >= i) v = A[(long)(p0 + i) * d + p0 + j];
-    s[i][j] = v;
-    x[i][j] = 0.0;
+    s[e / NB][e % NB] = src[e];
+    x[e / NB][e % NB] = 0.0;
   }
   __syncthreads();
   x[c][c] = 1.0 / s[c][c];
@@ -203,10 +203,9 @@ __global__ __launch_bounds__(64) void diag_inverse_kernel(const double* __restri
     x[i][c] = -acc / s[i][i];
   }
   __syncthreads();
-  double* out = Dinv + (long)blockIdx.x * NB * NB;
   for (int e = c; e < NB * NB; e += 64) {
     const int i = e / NB, j = e % NB;
-    out[e] = (i < nb && j < nb && j >= i) ? x[i][j] : 0.0;
+    if (i < nb && j < nb) A[(long)(p0 + i) * d + p0 + j] = (j >= i) ? x[i][j] : 0.0;
   }
 }
 
@@ -294,17 +293,6 @@ __global__ __launch_bounds__(256) void syrk_trailing_kernel(double* __restrict__
 }
 
 // ---------------------------------------------------------------- invert -------------------
-// Diagonal blocks of A <- R_pp^-1 (upper), strictly lower part of each block <- 0.
-__global__ __launch_bounds__(256) void put_diag_inverse_kernel(double* __restrict__ A, int d,
-                                                               const double* __restrict__ Dinv) {
-  const int p0 = blockIdx.x * NB;
-  const double* src = Dinv + (long)blockIdx.x * NB * NB;
-  for (int e = threadIdx.x; e < NB * NB; e += 256) {
-    const int i = e / NB, j = e % NB;
-    if (p0 + i < d && p0 + j < d) A[(long)(p0 + i) * d + p0 + j] = src[e];
-  }
-}
-
 // Node `node` of tree depth `depth` over the block range [0, P): ranges are halved
 // (left half gets the extra block).  Returns false if the path ends in a leaf earlier.
 __device__ __forceinline__ bool tree_node(int P, int depth, int node, int& lo, int& mid, int& hi) {
@@ -396,7 +384,7 @@ static int tree_depth(int P) {   // number of levels that contain at least one i
 }
 
 struct PrepLayout {
-  size_t a_off, tmp_off, dinv_off, scal_off, total;
+  size_t a_off, tmp_off, rdiag_off, scal_off, total;
   int P, ldt;
 };
 
@@ -407,7 +395,7 @@ static PrepLayout prep_layout(int d) {
   size_t off = 0;
   L.a_off = off;    off += bpdq_align_up((size_t)d * d * sizeof(double), 256);
   L.tmp_off = off;  off += bpdq_align_up((size_t)d * L.ldt * sizeof(double), 256);
-  L.dinv_off = off; off += bpdq_align_up((size_t)L.P * NB * NB * sizeof(double), 256);
+  L.rdiag_off = off; off += bpdq_align_up((size_t)L.P * NB * NB * sizeof(double), 256);
   L.scal_off = off; off += 256;
   L.total = off;
   return L;
@@ -436,7 +424,7 @@ extern "C" int bpdq_prepare(const float* H, int d_in, float damp, float* U, unsi
   char* base = static_cast<char*>(ws);
   double* A = reinterpret_cast<double*>(base + L.a_off);
   double* tmp = reinterpret_cast<double*>(base + L.tmp_off);
-  double* Dinv = reinterpret_cast<double*>(base + L.dinv_off);
+  double* Rdiag = reinterpret_cast<double*>(base + L.rdiag_off);
   double* scal = reinterpret_cast<double*>(base + L.scal_off);
   const int d = d_in, P = L.P;
 
@@ -450,7 +438,7 @@ extern "C" int bpdq_prepare(const float* H, int d_in, float damp, float* U, unsi
     const int p0 = p * NB;
     const int nb = (d - p0 < NB) ? d - p0 : NB;
     hipLaunchKernelGGL(panel_factor_kernel, dim3(p > 0 ? p : 1), dim3(256), 0, stream, A, d, p0, nb,
-                       p, info);
+                       p, Rdiag + (size_t)p * NB * NB, info);
     BPDQ_LAUNCH_CHECK();
     if (p > 0) {
       hipLaunchKernelGGL(syrk_trailing_kernel, dim3(p * (p + 1) / 2), dim3(256), 0, stream, A, d,
@@ -459,9 +447,7 @@ extern "C" int bpdq_prepare(const float* H, int d_in, float damp, float* U, unsi
     }
   }
 
-  hipLaunchKernelGGL(diag_inverse_kernel, dim3(P), dim3(64), 0, stream, A, d, Dinv);
-  BPDQ_LAUNCH_CHECK();
-  hipLaunchKernelGGL(put_diag_inverse_kernel, dim3(P), dim3(256), 0, stream, A, d, Dinv);
+  hipLaunchKernelGGL(diag_inverse_kernel, dim3(P), dim3(64), 0, stream, Rdiag, A, d);
   BPDQ_LAUNCH_CHECK();
   const int depth = tree_depth(P);
   for (int dd = depth - 1; dd >= 0; --dd) {

@@ -71,8 +71,15 @@ def _end_to_end(dev, wl, tokens_per_call=0):
     _log(f"{wl.name}: oracle prepare done")
     u_err = float(np.linalg.norm(U.cpu().numpy() - Uref) / np.linalg.norm(Uref))
     Wn = W.cpu().numpy()
+    last = [time.time()]
+
+    def progress(done, total):
+        if time.time() - last[0] > 45:
+            last[0] = time.time()
+            _log(f"{wl.name}: oracle sweep at column {done} of {total}")
+
     ref = orc.quantize_layer(Wn, Uref, dead_ref, wl.bits, wl.group, wl.block, wl.refine_iters,
-                             alpha=float(np.float32(wl.alpha)))
+                             alpha=float(np.float32(wl.alpha)), progress=progress)
     _log(f"{wl.name}: oracle sweep done")
     code = orc.unpack_planes(out["planes"].cpu().numpy().view(np.uint32), d_in)
     nd = sum(int(np.sum(((code >> i) & 1) != ((ref["code"] >> i) & 1))) for i in range(wl.bits))

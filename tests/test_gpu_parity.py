@@ -278,3 +278,26 @@ def test_pack_and_dequant_bit_exact(dev, bits):
         want = np.where(b, (want + np.repeat(coef[i], group, axis=1)).astype(np.float32), want)
     assert np.array_equal(Wg, want)
     assert np.allclose(Wg, orc.dequant(pg, coef, group), rtol=1e-6, atol=1e-7)
+
+
+def test_prepare_many_panels_defining_property(dev):
+    """A width whose panel launches have more work-groups than the chip holds at once
+    (18944 = 296 panels): checked through the defining property U^T U (H + lambda I) = I on
+    sampled columns, evaluated in fp64 by torch (neither side's code)."""
+    print("prepare d_in=18944 (property check)", flush=True)
+    d, ntok = 18944, 4096
+    g = torch.Generator(device=dev)
+    g.manual_seed(11)
+    X = torch.randn((ntok, d), device=dev, generator=g)
+    H = torch.zeros((d, d), device=dev)
+    bq.bpdq_hessian_accumulate(X, H, symmetrize=True)
+    H.diagonal().add_(float(H.diagonal().mean()))        # well conditioned although N < d
+    U, dead, info = bq.bpdq_prepare(H, 0.01)
+    torch.cuda.synchronize()
+    assert int(info.item()) == 0
+    idx = torch.arange(0, d, d // 48, device=dev)[:48]
+    Ht = H.double()
+    Ht.diagonal().add_(0.01 * float(H.diagonal().mean()))
+    R = U.double().T @ (U.double() @ Ht[:, idx])
+    R[idx, torch.arange(len(idx), device=dev)] -= 1.0
+    assert float(R.abs().max()) < 1e-5
