@@ -4,9 +4,10 @@
   tokens) runs at FULL size, in the launch configuration bench.py times (one Hessian call
   over all tokens), against the full oracle.
 * The other four run by default at 1/8 of their linear dimensions with their own value
-  distributions and knobs; with BPDQ_FULL_CONFIGS=1 they run at full shape (tokens reduced so
-  that the fp64 oracle finishes), and the full-token Hessian is checked on sampled
-  sub-matrices, which the oracle computes exactly from the sampled input channels.
+  distributions and knobs; with BPDQ_FULL_CONFIGS=1 they run at full shape and token count
+  (minutes of host fp64 work each; BPDQ_FULL_TOKENS=<n> shortens the token axis), and the
+  full-token Hessian is also checked on sampled sub-matrices, which the oracle computes exactly
+  from the sampled input channels.
 """
 import os
 import time
@@ -60,8 +61,12 @@ def _end_to_end(dev, wl, tokens_per_call=0):
     _log(f"{wl.name}: gpu pass done")
     # ---- oracle on the same buffers
     Href = np.zeros((d_in, d_in))
+    last = [time.time()]
     for c in range(wk.n_chunks(wl)):
         orc.hessian_accumulate(X[c * wl.chunk:(c + 1) * wl.chunk].cpu().numpy(), Href)
+        if time.time() - last[0] > 45:
+            last[0] = time.time()
+            _log(f"{wl.name}: oracle H at chunk {c + 1} of {wk.n_chunks(wl)}")
     _log(f"{wl.name}: oracle H done")
     Hg = H.cpu().numpy().astype(np.float64)
     h_err = float(np.linalg.norm(Hg - Href) / np.linalg.norm(Href))
@@ -71,8 +76,6 @@ def _end_to_end(dev, wl, tokens_per_call=0):
     _log(f"{wl.name}: oracle prepare done")
     u_err = float(np.linalg.norm(U.cpu().numpy() - Uref) / np.linalg.norm(Uref))
     Wn = W.cpu().numpy()
-    last = [time.time()]
-
     def progress(done, total):
         if time.time() - last[0] > 45:
             last[0] = time.time()
@@ -131,18 +134,20 @@ def test_other_workloads_scaled(dev, name):
 
 
 FULL_SHAPES = {
-    # full layer shape; tokens reduced so that the fp64 oracle finishes on the host
-    "cfg3a_qwen7b_up": 32768,
-    "cfg3b_qwen7b_down": 32768,
-    "cfg4_qwen72b_attn": 32768,
-    "cfg5_qwen72b_down": 32768,
+    # full layer shape and token count; BPDQ_FULL_TOKENS=<n> reduces the tokens (the fp64
+    # oracle Hessian of the widest layer takes minutes of host time at all 262144)
+    "cfg3a_qwen7b_up": 262144,
+    "cfg3b_qwen7b_down": 262144,
+    "cfg4_qwen72b_attn": 262144,
+    "cfg5_qwen72b_down": 262144,
 }
+FULL_TOKENS = int(os.environ.get("BPDQ_FULL_TOKENS", "0"))
 
 
 @pytest.mark.skipif(not FULL, reason="set BPDQ_FULL_CONFIGS=1 (minutes of host fp64 work per case)")
 @pytest.mark.parametrize("name", sorted(FULL_SHAPES))
 def test_other_workloads_full_shape(dev, name):
-    wl = wk.WORKLOADS[name].scaled(n_tok=FULL_SHAPES[name])
+    wl = wk.WORKLOADS[name].scaled(n_tok=FULL_TOKENS or FULL_SHAPES[name])
     _end_to_end(dev, wl, tokens_per_call=4096)
 
 
