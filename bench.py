@@ -164,7 +164,7 @@ def main():
     launch_ms = phase_ms["hessian"] / len(calls)
     achieved = flops_per_launch / (launch_ms * 1e-3) / 1e12 if launch_ms > 0 else 0.0
     traffic = None
-    tp = os.path.join(ROOT, "profiles", f"hess_syrk_{args.workload}_traffic.json")
+    tp = os.path.join(ROOT, "profiles", f"hess_syrk_{args.workload}_traffic.json")   # from rocprofv3 --pmc runs
     if os.path.exists(tp) and len(calls) == 1:
         traffic = json.load(open(tp)).get("hbm_bytes_per_launch")
     res = {
