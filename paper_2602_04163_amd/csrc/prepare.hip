@@ -8,8 +8,10 @@
 // workspace; the result is rounded to fp32 once, on output.
 //
 //   factor : right-looking over 64-column panels from the right: every panel work-group factors
-//            the diagonal block in registers and solves its 64 rows of R12 R22^T = A12, then the
-//            trailing update A11 -= R12 R12^T runs on the upper 64 x 64 tiles.
+//            the diagonal block in registers and solves its 64 rows of R12 R22^T = A12.  The
+//            trailing update A11 -= R12 R12^T (fp64 MFMA, upper 64 x 64 tiles) is two-level:
+//            after each panel only inside the current 512-column outer panel, and once per
+//            outer panel, with K = 512, on everything to its left.
 //   invert : divide and conquer over block ranges, [R11 R12; 0 R22]^-1 =
 //            [U11, -U11 R12 U22; 0, U22]; every tree level is two launches.
 #include "common.h"
@@ -264,31 +266,40 @@ __device__ __forceinline__ void quad_for_each(const Quad64& q, F f) {
           q.c[i][j][r]);
 }
 
-// Trailing update on the upper 64 x 64 tiles of the leading p0 x p0 block:
-// A11[i][j] -= sum_k R12[i][k] R12[j][k], k over the nb panel columns.
-__global__ __launch_bounds__(256) void syrk_trailing_kernel(double* __restrict__ A, int d, int p0,
-                                                            int nb, int nblk) {
+// Trailing update with the panel columns [k0, k0 + Kd):  A[i][j] -= sum_k A[i][k] A[j][k]  on the
+// upper 64 x 64 tiles (bi <= bj) whose block column bj lies in [cb0, cb1).  Used twice:
+//   inner: after each 64-column panel, only for the block columns of the same outer panel that
+//          are still to be factored (Kd = 64);
+//   outer: once per outer panel, for everything to its left (Kd = outer width, up to 512), so
+//          the big trailing matrix is read and written 8 times less often.
+__global__ __launch_bounds__(256) void syrk_trailing_kernel(double* __restrict__ A, int d, int k0,
+                                                            int Kd, int cb0, int cb1) {
   __shared__ double si[NB][NB + 1];
   __shared__ double sj[NB][NB + 1];
-  int tile = blockIdx.x, bi = 0;
-  while (tile >= nblk - bi) {
-    tile -= nblk - bi;
-    ++bi;
+  int tile = blockIdx.x, bj = cb0;
+  while (tile >= bj + 1) {
+    tile -= bj + 1;
+    ++bj;
   }
-  const int bj = bi + tile;
+  const int bi = tile;
   const int tid = threadIdx.x;
-  for (int e = tid; e < NB * NB; e += 256) {
-    const int i = e / NB, k = e % NB;
-    si[i][k] = (bi * NB + i < p0 && k < nb) ? A[(long)(bi * NB + i) * d + p0 + k] : 0.0;
-    sj[i][k] = (bj * NB + i < p0 && k < nb) ? A[(long)(bj * NB + i) * d + p0 + k] : 0.0;
-  }
-  __syncthreads();
+  const int k_end = (k0 + Kd < d) ? k0 + Kd : d;
   Quad64 q;
   quad_zero(q);
-  quad_mfma_64<true>(si, sj, q);
+  for (int kc = k0; kc < k_end; kc += NB) {
+    for (int e = tid; e < NB * NB; e += 256) {
+      const int i = e / NB, k = e % NB;
+      const bool in = kc + k < k_end;
+      si[i][k] = in ? A[(long)(bi * NB + i) * d + kc + k] : 0.0;
+      sj[i][k] = in ? A[(long)(bj * NB + i) * d + kc + k] : 0.0;
+    }
+    __syncthreads();
+    quad_mfma_64<true>(si, sj, q);
+    __syncthreads();
+  }
   quad_for_each(q, [&](int r, int c, double v) {
     const int i = bi * NB + r, j = bj * NB + c;
-    if (i < p0 && j < p0 && j >= i) A[(long)i * d + j] -= v;
+    if (j >= i) A[(long)i * d + j] -= v;
   });
 }
 
@@ -434,15 +445,26 @@ extern "C" int bpdq_prepare(const float* H, int d_in, float damp, float* U, unsi
   hipLaunchKernelGGL(prep_load_kernel, dim3(grid_el), dim3(256), 0, stream, H, d, scal, A);
   BPDQ_LAUNCH_CHECK();
 
-  for (int p = P - 1; p >= 0; --p) {
-    const int p0 = p * NB;
-    const int nb = (d - p0 < NB) ? d - p0 : NB;
-    hipLaunchKernelGGL(panel_factor_kernel, dim3(p > 0 ? p : 1), dim3(256), 0, stream, A, d, p0, nb,
-                       p, Rdiag + (size_t)p * NB * NB, info);
-    BPDQ_LAUNCH_CHECK();
-    if (p > 0) {
-      hipLaunchKernelGGL(syrk_trailing_kernel, dim3(p * (p + 1) / 2), dim3(256), 0, stream, A, d,
-                         p0, nb, p);
+  // outer panels of kOuter blocks, from the right; inside one, 64-column panels from the right
+  constexpr int kOuter = 8;
+  for (int ob1 = P; ob1 > 0; ob1 -= kOuter) {
+    const int ob0 = ob1 > kOuter ? ob1 - kOuter : 0;
+    for (int p = ob1 - 1; p >= ob0; --p) {
+      const int p0 = p * NB;
+      const int nb = (d - p0 < NB) ? d - p0 : NB;
+      hipLaunchKernelGGL(panel_factor_kernel, dim3(p > 0 ? p : 1), dim3(256), 0, stream, A, d, p0,
+                         nb, p, Rdiag + (size_t)p * NB * NB, info);
+      BPDQ_LAUNCH_CHECK();
+      if (p > ob0) {
+        const int tiles = (p * (p + 1) - ob0 * (ob0 + 1)) / 2;
+        hipLaunchKernelGGL(syrk_trailing_kernel, dim3(tiles), dim3(256), 0, stream, A, d, p0, nb,
+                           ob0, p);
+        BPDQ_LAUNCH_CHECK();
+      }
+    }
+    if (ob0 > 0) {
+      hipLaunchKernelGGL(syrk_trailing_kernel, dim3(ob0 * (ob0 + 1) / 2), dim3(256), 0, stream, A, d,
+                         ob0 * NB, (ob1 - ob0) * NB, 0, ob0);
       BPDQ_LAUNCH_CHECK();
     }
   }
