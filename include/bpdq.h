@@ -30,19 +30,24 @@ extern "C" {
 #endif
 
 #define BPDQ_ERR_LAUNCH (-100)
+#define BPDQ_GRID_VARIABLE 0
+#define BPDQ_GRID_UNIFORM 1
 
 /* Knobs of the method (paper Sec. 4.1: k in {2,3,4}, g in {64,128,256}, 10 iterations,
  * alpha = 1e-4). */
 typedef struct bpdq_params {
   int   bits;           /* k, number of bit-planes: 1..4                                      */
-  int   group;          /* g: 32, 64 or 128; must divide d_in                                 */
+  int   group;          /* g: 32, 64, 128 or 256; must divide d_in                            */
   int   block;          /* lazy-update block B; the effective block is max(B, g); g | B       */
   int   refine_iters;   /* T >= 0 iterations of (bit-plane update, refit, delta correction);
                            0 keeps the initialisation + one fit (Sec. 3.2)                    */
   float alpha;          /* relative ridge of the coefficient fit (Sec. 3.2, end): the
                            (k+1)x(k+1) normal matrix G gets alpha*tr(G)/(k+1) on its diagonal */
-  int   select_per_row; /* 0: keep the iterate with the smallest group-wise ||E||_F^2 over all
-                           rows (Sec. 3.3).  Other values are rejected.                       */
+  int   grid;           /* BPDQ_GRID_VARIABLE: the method (variable grid, Sec. 3).
+                           BPDQ_GRID_UNIFORM: the fixed-grid comparator of App. A -- levels
+                           lo + s*{0..2^k-1} per (row, group) from the group's min/max, one
+                           sweep, no fit (GPTQ on a uniform grid); refine_iters and alpha are
+                           ignored, the coefficients returned are (lo, s, 2s, ...).             */
 } bpdq_params;
 
 /* Library version (major*10000 + minor*100 + patch). */

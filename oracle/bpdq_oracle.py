@@ -48,7 +48,7 @@ from scipy.linalg import solve_triangular
 __all__ = [
     "hessian_accumulate", "prepare", "init_codes", "design_matrix", "fit_coefficients",
     "level_table", "nearest_level", "bitplane_sweep", "reconstruct", "solve_right",
-    "bpdq_group", "quantize_layer", "pack_planes", "unpack_planes", "dequant",
+    "bpdq_group", "uniform_frozen_group", "quantize_layer", "pack_planes", "unpack_planes", "dequant",
     "layer_objective", "bits_per_weight",
 ]
 
@@ -250,6 +250,22 @@ def bpdq_group(T, UL, k, refine_iters, alpha=1e-4, select_per_row=False,
             best["it"] = np.where(take, t, best["it"]).astype(np.int32)
     best["score"] = best["rowscore"] if select_per_row else float(best["rowscore"].sum())
     return best
+
+
+def uniform_frozen_group(T, UL, k, decision_dtype=np.float32):
+    """The fixed uniform grid written as a variable grid (App. A, Prop. 1): coefficients frozen
+    to (lo, s, 2s, 4s, ...), s = (hi - lo) / (2^k - 1) from the group-start block's per-row
+    min / max (a flat row gets s = 1), one bit-plane update pass, no fit, no iteration.  This is
+    GPTQ on the asymmetric min/max grid; `uniform_gptq.uniform_group` states the same thing with
+    round-to-nearest on the integer grid and the two are pinned to each other."""
+    T = np.asarray(T, dtype=np.float64)
+    lo = T.min(axis=1)
+    hi = T.max(axis=1)
+    s = (hi - lo) / float((1 << k) - 1)
+    s = np.where(s == 0.0, 1.0, s)
+    c = np.stack([lo] + [s * (1 << i) for i in range(k)], axis=1)
+    code, What, E = bitplane_sweep(T, UL, c, k, decision_dtype)
+    return dict(code=code, coef=c, What=What, E=E, it=np.zeros(T.shape[0], dtype=np.int32))
 
 
 # --------------------------------------------------------------------------- #

@@ -27,7 +27,7 @@ EXPORTS = [
 class BpdqParams(ctypes.Structure):
     _fields_ = [("bits", ctypes.c_int), ("group", ctypes.c_int), ("block", ctypes.c_int),
                 ("refine_iters", ctypes.c_int), ("alpha", ctypes.c_float),
-                ("select_per_row", ctypes.c_int)]
+                ("grid", ctypes.c_int)]
 
 
 class BpdqError(RuntimeError):
@@ -138,8 +138,11 @@ def bpdq_prepare(H, damp=0.01, U=None, ws=None):
     return U, dead, info
 
 
-def make_params(bits, group, block, refine_iters, alpha=1e-4, select_per_row=0) -> BpdqParams:
-    return BpdqParams(bits, group, block, refine_iters, alpha, select_per_row)
+GRID_VARIABLE, GRID_UNIFORM = 0, 1
+
+
+def make_params(bits, group, block, refine_iters, alpha=1e-4, grid=GRID_VARIABLE) -> BpdqParams:
+    return BpdqParams(bits, group, block, refine_iters, alpha, grid)
 
 
 def bpdq_quantize_workspace_bytes(d_out, d_in, params: BpdqParams) -> int:

@@ -11,8 +11,10 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbpdq.so")
-SOURCES = ["hessian.hip", "prepare.hip", "quantize.hip", "group_sweep_k1.hip", "group_sweep_k2.hip",
-           "group_sweep_k3.hip", "group_sweep_k4.hip"]
+# the heaviest translation units first: the pool starts them first
+SOURCES = ["group_sweep_k4_g256.hip", "group_sweep_k3_g256.hip", "group_sweep_k4.hip",
+           "group_sweep_k2_g256.hip", "group_sweep_k3.hip", "group_sweep_k1_g256.hip",
+           "group_sweep_k2.hip", "group_sweep_k1.hip", "hessian.hip", "prepare.hip", "quantize.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -43,7 +45,7 @@ def build(verbose: bool = True) -> str:
     for src in SOURCES:
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
         jobs.append(([hipcc] + compile_flags + ["-c", os.path.join(CSRC, src), "-o", obj], obj))
-    with ThreadPoolExecutor(max_workers=len(jobs)) as ex:
+    with ThreadPoolExecutor(max_workers=min(len(jobs), os.cpu_count() or 4)) as ex:
         list(ex.map(lambda j: _run(j[0], verbose), jobs))
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + [j[1] for j in jobs] + ["-o", LIB],
          verbose)

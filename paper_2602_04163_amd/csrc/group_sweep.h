@@ -33,8 +33,10 @@ constexpr int kSweepThreads = 256;
 // ------------------------------------------------------------------ lane helpers -----------
 template <int CTRL>
 __device__ __forceinline__ float dpp_f(float x) {
-  return __builtin_bit_cast(
-      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, false));
+  // every lane reads a valid lane of its own row, so the "old" operand is never used: passing x
+  // itself spares the compiler a zero-initialisation per DPP move
+  const int xi = __builtin_bit_cast(int, x);
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(xi, xi, CTRL, 0xF, 0xF, false));
 }
 template <int CTRL>
 __device__ __forceinline__ double dpp_d(double x) {
@@ -78,22 +80,102 @@ struct RowState {
   int code[CPL];      // plane bits of my columns, bit (i-1) = B_i
 };
 
-// One column of the forward recurrence.  SWEEP = false: initial pass (codes known, also
-// builds tau and P_0).  SWEEP = true: bit-plane update of column L (Eq. 7-8), its error
-// coordinate (Eq. 3) and compensation of the later columns (Eq. 4), plus the plane solves.
-template <int K, int G, int L, bool SWEEP>
+// LDS layout of the local factor.  Row l only ever meets columns j > l, and column j lives in
+// slot j / 16 of lane j % 16, so row l keeps just the S = CPL - l / 16 slots m >= M = l / 16 of
+// every lane: 16 S floats, no padding.  The slots are cut into chunks of 4, then 2, then 1
+// (S = 7 -> 4 + 2 + 1); a chunk of width w that starts at slot M + o holds
+//   sU[row_offset(l) + 16 o + lane * w + e] = U[l][16 (M + o + e) + lane]     (0 where j <= l)
+// so one ds_read_b128 / b64 / b32 of the 16 lanes of a row covers 16 w contiguous floats (no bank
+// conflicts) at an immediate offset, no register is loaded that the step does not use, and the
+// lower part reads as zero (no masks in the inner loop).  36 KB at g = 128, 136 KB at g = 256.
+template <int G>
+struct SuLayout {
+  static constexpr int CPL = G / 16;
+  static constexpr int live(int M) { return CPL - M; }
+  static constexpr int row_offset(int l) {
+    int off = 0;
+    for (int M = 0; M < l / 16; ++M) off += 256 * live(M);
+    return off + 16 * (l % 16) * live(l / 16);
+  }
+  static constexpr int floats() { return row_offset(G); }
+  // widest chunk: 4 floats (ds_read_b128); 2 at g = 256, where the wider reads push the
+  // fully unrolled sweep over the register file
+  static constexpr int kMaxVec = (G >= 256) ? 2 : 4;
+  // width of the chunk that holds live slot o (0-based among the live slots) of a row with S
+  // live slots, and the live slot that chunk starts at
+  static constexpr int chunk_width(int S, int o) {
+    const int g0 = o / kMaxVec * kMaxVec, r = S - g0, i = o - g0;
+    if (r >= kMaxVec) return kMaxVec;     // a full chunk
+    return (r >= 2 && i < 2) ? 2 : 1;     // r = 3: 2 + 1;  r = 2: 2;  r = 1: 1
+  }
+  static constexpr int chunk_start(int S, int o) {
+    const int g0 = o / kMaxVec * kMaxVec, r = S - g0, i = o - g0;
+    if (r >= kMaxVec) return g0;
+    return (r >= 2 && i < 2) ? g0 : g0 + i;
+  }
+  // float index (relative to the row) of live slot o for lane `lane`
+  static constexpr int slot_index(int S, int o, int lane) {
+    const int w = chunk_width(S, o), c0 = chunk_start(S, o);
+    return 16 * c0 + lane * w + (o - c0);
+  }
+};
+
+// the live slots [M, CPL) of one row for this lane; p = sU + row_offset(l)
+template <int G, int M>
+__device__ __forceinline__ void load_u_row(const float* __restrict__ p, int lane16,
+                                           float (&u)[G / 16]) {
+  using Lay = SuLayout<G>;
+  constexpr int CPL = G / 16, S = CPL - M;
+  typedef float vec4 __attribute__((ext_vector_type(4)));
+  typedef float vec2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+  for (int o = 0; o < S; ++o) {
+    if (Lay::chunk_start(S, o) != o) continue;
+    const int w = Lay::chunk_width(S, o);
+    if (w == 4) {
+      const vec4 v = *reinterpret_cast<const vec4*>(p + 16 * o + lane16 * 4);
+      u[M + o] = v[0]; u[M + o + 1] = v[1]; u[M + o + 2] = v[2]; u[M + o + 3] = v[3];
+    } else if (w == 2) {
+      const vec2 v = *reinterpret_cast<const vec2*>(p + 16 * o + lane16 * 2);
+      u[M + o] = v[0]; u[M + o + 1] = v[1];
+    } else {
+      u[M + o] = p[16 * o + lane16];
+    }
+  }
+}
+
+enum : int { kStepInit = 0, kStepSweep = 1, kStepUniform = 2 };
+
+// One column of the forward recurrence.
+//   kStepInit:    initial pass (codes known): builds tau, P_0 and the plane solves P_i.
+//   kStepSweep:   bit-plane update of column L (Eq. 7-8), its error coordinate (Eq. 3),
+//                 compensation of the later columns (Eq. 4), and the plane solves.
+//   kStepUniform: the same column update with frozen coefficients and nothing else: the error
+//                 coordinates themselves are kept in st.tau (fixed-grid GPTQ comparator).
+// Row L of the local factor (`u`, `inv` = 1 / U_LL) arrives in registers; the step first issues
+// the LDS reads of row L + 1 and hands them over at its end, so that their latency overlaps this
+// column's arithmetic (one wave per SIMD: nothing else would hide it).
+template <int K, int G, int L, int MODE>
 __device__ __forceinline__ void column_step(RowState<K, G>& st, const float* __restrict__ sU,
                                             const float* __restrict__ sInv,
-                                            const float (&lv)[1 << K], int lane16) {
+                                            const float (&lv)[1 << K], int lane16,
+                                            float (&u)[G / 16], float& inv) {
   constexpr int CPL = G / 16, M = L / 16, O = L % 16;
-  const float inv = sInv[L];
   const bool owner = (lane16 == O);
-  float u[CPL];
-#pragma unroll
-  for (int m = M; m < CPL; ++m) u[m] = sU[L * G + lane16 * CPL + m];
-
+  constexpr bool kPinState = true;
+  constexpr bool kPrefetch = true;
+  float un[CPL];
+  float invn = 0.f;
+  if constexpr (!kPrefetch) {
+    load_u_row<G, M>(sU + SuLayout<G>::row_offset(L), lane16, u);
+    inv = sInv[L];
+  } else if constexpr (L + 1 < G) {
+    load_u_row<G, (L + 1) / 16>(sU + SuLayout<G>::row_offset(L + 1), lane16, un);
+    invn = sInv[L + 1];
+    __builtin_amdgcn_sched_barrier(0);   // keep the reads ahead of the arithmetic below
+  }
   float x[K], xb[K];
-  if constexpr (SWEEP) {
+  if constexpr (MODE != kStepInit) {
     const float w = st.wg[M];
     float diff = w - lv[0];
     float bd = diff * diff;
@@ -109,9 +191,13 @@ __device__ __forceinline__ void column_step(RowState<K, G>& st, const float* __r
       bc = lt ? c : bc;
     }
     const float e = (w - bq) * inv;
-#pragma unroll
-    for (int i = 0; i < K; ++i) x[i] = ((float)((bc >> i) & 1) + st.P[i][M]) * inv;
     if (owner) st.code[M] = bc;
+    if constexpr (MODE == kStepUniform) {
+      if (owner) st.tau[M] = e;
+    } else {
+#pragma unroll
+      for (int i = 0; i < K; ++i) x[i] = ((float)((bc >> i) & 1) + st.P[i][M]) * inv;
+    }
     const float eb = bcast16<O>(e);
 #pragma unroll
     for (int m = M; m < CPL; ++m) st.wg[m] = fmaf(-eb, u[m], st.wg[m]);
@@ -132,20 +218,64 @@ __device__ __forceinline__ void column_step(RowState<K, G>& st, const float* __r
       st.p0[m] = fmaf(-ob, u[m], st.p0[m]);
     }
   }
+  if constexpr (MODE != kStepUniform) {
 #pragma unroll
-  for (int i = 0; i < K; ++i) {
-    if (owner) st.P[i][M] = x[i];
-    xb[i] = bcast16<O>(x[i]);
+    for (int i = 0; i < K; ++i) {
+      if (owner) st.P[i][M] = x[i];
+      xb[i] = bcast16<O>(x[i]);
 #pragma unroll
-    for (int m = M; m < CPL; ++m) st.P[i][m] = fmaf(-xb[i], u[m], st.P[i][m]);
+      for (int m = M; m < CPL; ++m) st.P[i][m] = fmaf(-xb[i], u[m], st.P[i][m]);
+    }
+  }
+  // The updates of far slots are not consumed for many steps; left alone, instruction selection
+  // lets them drift there, together with the factor rows they need (hundreds of live registers).
+  // Empty asm statements with the values as in/out operands pin them to this step.
+  if constexpr (kPinState) {
+#pragma unroll
+    for (int m = M; m < CPL; ++m) {
+      if constexpr (MODE != kStepInit) asm volatile("" : "+v"(st.wg[m]));
+      if constexpr (MODE == kStepInit) asm volatile("" : "+v"(st.tau[m]), "+v"(st.p0[m]));
+      if constexpr (MODE != kStepUniform) {
+#pragma unroll
+        for (int i = 0; i < K; ++i) asm volatile("" : "+v"(st.P[i][m]));
+      }
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);     // later steps' reads stay behind this step
+  if constexpr (kPrefetch && L + 1 < G) {
+#pragma unroll
+    for (int m = (L + 1) / 16; m < CPL; ++m) u[m] = un[m];
+    inv = invn;
   }
 }
 
-template <int K, int G, bool SWEEP, int... Ls>
+template <int K, int G, int MODE, int... Ls>
 __device__ __forceinline__ void run_columns(RowState<K, G>& st, const float* sU, const float* sInv,
                                             const float (&lv)[1 << K], int lane16,
                                             std::integer_sequence<int, Ls...>) {
-  (column_step<K, G, Ls, SWEEP>(st, sU, sInv, lv, lane16), ...);
+  float u[G / 16];
+  load_u_row<G, 0>(sU, lane16, u);
+  float inv = sInv[0];
+  (column_step<K, G, Ls, MODE>(st, sU, sInv, lv, lane16, u, inv), ...);
+}
+
+// Stage the local factor U[s0:s0+G, s0:s0+G] in LDS (layout above) and 1 / U_ll in sInv.
+template <int G>
+__device__ __forceinline__ void stage_local_factor(const float* __restrict__ U, int ldu, int s0,
+                                                   float* sU, float* sInv) {
+  using Lay = SuLayout<G>;
+  for (int e = threadIdx.x; e < G * G; e += kSweepThreads) {
+    const int l = e / G, j = e % G;
+    const int M = l >> 4, m = j >> 4;
+    if (m >= M) {
+      const float v = U[(long)(s0 + l) * ldu + s0 + j];
+      int off = 0;
+      for (int q = 0; q < M; ++q) off += 256 * Lay::live(q);
+      off += 16 * (l & 15) * Lay::live(M);
+      sU[off + Lay::slot_index(Lay::live(M), m - M, j & 15)] = (j > l) ? v : 0.f;
+      if (j == l) sInv[l] = 1.0f / v;
+    }
+  }
 }
 
 // Coefficient fit (Eq. 6) from the solved vectors; returns c (fp32) and the row's ||E'||^2.
@@ -280,17 +410,12 @@ __global__ __launch_bounds__(kSweepThreads) void bpdq_group_kernel(
     float* __restrict__ cand_E, double* __restrict__ cand_score) {
   constexpr int CPL = G / 16;
   extern __shared__ float lds[];
-  float* sU = lds;                 // [G][16][CPL], zero on and below the diagonal
-  float* sInv = lds + G * G;       // 1 / U_ll
-  double* sScore = reinterpret_cast<double*>(lds + G * G + G);
+  float* sU = lds;                            // packed local factor, see SuLayout
+  float* sInv = lds + SuLayout<G>::floats();          // 1 / U_ll
+  double* sScore = reinterpret_cast<double*>(lds + SuLayout<G>::floats() + G);
   const int tid = threadIdx.x;
   const int lane16 = tid & 15;
-  for (int e = tid; e < G * G; e += kSweepThreads) {
-    const int l = e / G, j = e % G;
-    const float v = U[(long)(s0 + l) * ldu + s0 + j];
-    sU[l * G + (j & 15) * CPL + (j >> 4)] = (j > l) ? v : 0.f;
-    if (j == l) sInv[l] = 1.0f / v;
-  }
+  stage_local_factor<G>(U, ldu, s0, sU, sInv);
   __syncthreads();
 
   const int row = blockIdx.x * kRowsPerWG + (tid >> 4);
@@ -327,7 +452,7 @@ __global__ __launch_bounds__(kSweepThreads) void bpdq_group_kernel(
 #pragma unroll
   for (int c = 0; c < (1 << K); ++c) lv[c] = 0.f;
   using Seq = std::make_integer_sequence<int, G>;
-  run_columns<K, G, false>(st, sU, sInv, lv, lane16, Seq{});
+  run_columns<K, G, kStepInit>(st, sU, sInv, lv, lane16, Seq{});
 
   const int n_wg = gridDim.x;
   float c32[K + 1], Ep[CPL];
@@ -344,11 +469,71 @@ __global__ __launch_bounds__(kSweepThreads) void bpdq_group_kernel(
 #pragma unroll
       for (int i = 0; i < K; ++i) st.P[i][m] = 0.f;
     }
-    run_columns<K, G, true>(st, sU, sInv, lv, lane16, Seq{});
+    run_columns<K, G, kStepSweep>(st, sU, sInv, lv, lane16, Seq{});
     rs = fit_and_score<K, G>(st, (double)alpha, c32, Ep);
     store_candidate<K, G>(st, c32, Ep, rs, it, row, valid, d_out, n_wg, cand_codes, cand_coef,
                           cand_E, cand_score, sScore, lane16);
   }
+}
+
+// Fixed-uniform-grid comparator (App. A, "Fixed Grid"): the same column sweep with the levels
+// frozen to lo + s * {0 .. 2^k - 1}, s = (hi - lo) / (2^k - 1), written as bit-plane coefficients
+// (lo, s, 2s, 4s, ...) -- the special case of Prop. 1.  One pass, no fit, no iteration: this is
+// GPTQ on the asymmetric min/max grid.  The result is stored as iterate 0.
+template <int K, int G>
+__global__ __launch_bounds__(kSweepThreads) void uniform_group_kernel(
+    const float* __restrict__ Wp, int ldw, int d_out, const float* __restrict__ U, int ldu, int s0,
+    unsigned char* __restrict__ cand_codes, float* __restrict__ cand_coef,
+    float* __restrict__ cand_E, double* __restrict__ cand_score) {
+  constexpr int CPL = G / 16;
+  extern __shared__ float lds[];
+  float* sU = lds;
+  float* sInv = lds + SuLayout<G>::floats();
+  double* sScore = reinterpret_cast<double*>(lds + SuLayout<G>::floats() + G);
+  const int tid = threadIdx.x;
+  const int lane16 = tid & 15;
+  stage_local_factor<G>(U, ldu, s0, sU, sInv);
+  __syncthreads();
+
+  const int row = blockIdx.x * kRowsPerWG + (tid >> 4);
+  const bool valid = row < d_out;
+  const int rr = valid ? row : d_out - 1;
+  RowState<K, G> st;
+  const float* wrow = Wp + (long)rr * ldw + s0;
+#pragma unroll
+  for (int m = 0; m < CPL; ++m) st.t[m] = wrow[16 * m + lane16];
+  float lo = st.t[0], hi = st.t[0];
+#pragma unroll
+  for (int m = 1; m < CPL; ++m) {
+    lo = fminf(lo, st.t[m]);
+    hi = fmaxf(hi, st.t[m]);
+  }
+  lo = row_reduce_f(lo, [](float a, float b) { return fminf(a, b); });
+  hi = row_reduce_f(hi, [](float a, float b) { return fmaxf(a, b); });
+  float step = (hi - lo) / (float)((1 << K) - 1);
+  if (step == 0.f) step = 1.0f;                 // flat row: every weight takes code 0
+  float c32[K + 1], lv[1 << K], Ep[CPL];
+  c32[0] = lo;
+#pragma unroll
+  for (int i = 0; i < K; ++i) c32[i + 1] = step * (float)(1 << i);
+  level_table<K>(c32, lv);
+#pragma unroll
+  for (int m = 0; m < CPL; ++m) {
+    st.wg[m] = st.t[m];
+    st.tau[m] = 0.f;
+    st.code[m] = 0;
+  }
+  using Seq = std::make_integer_sequence<int, G>;
+  run_columns<K, G, kStepUniform>(st, sU, sInv, lv, lane16, Seq{});
+  double sc = 0.0;
+#pragma unroll
+  for (int m = 0; m < CPL; ++m) {
+    Ep[m] = st.tau[m];
+    sc += (double)Ep[m] * (double)Ep[m];
+  }
+  sc = row_sum_d(sc);
+  store_candidate<K, G>(st, c32, Ep, sc, 0, row, valid, d_out, gridDim.x, cand_codes, cand_coef,
+                        cand_E, cand_score, sScore, lane16);
 }
 
 // Selection + commit of one group, 16 rows per work-group (same lane mapping as the sweep).
@@ -472,20 +657,29 @@ static inline int launch_group(hipStream_t stream, const float* Wp, int d_out, i
   float* c_E = reinterpret_cast<float*>(base + L.e_off);
   double* c_score = reinterpret_cast<double*>(base + L.score_off);
   float* Eblk = reinterpret_cast<float*>(base + L.eblk_off);
-  const size_t lds = (size_t)(G * G + G) * sizeof(float) + kRowsPerWG * sizeof(double);
+  const size_t lds = (size_t)(SuLayout<G>::floats() + G) * sizeof(float) + kRowsPerWG * sizeof(double);
   static bool attr_set = false;
   if (!attr_set) {
     BPDQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(bpdq_group_kernel<K, G>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    BPDQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(uniform_group_kernel<K, G>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr_set = true;
   }
   const int gi = s0 / G;
-  hipLaunchKernelGGL((bpdq_group_kernel<K, G>), dim3(L.n_wg), dim3(kSweepThreads), lds, stream, Wp,
-                     d_in, d_out, U, d_in, s0, p.refine_iters, p.alpha, c_codes, c_coef, c_E, c_score);
+  const bool uniform = (p.grid == BPDQ_GRID_UNIFORM);
+  const int T = uniform ? 0 : p.refine_iters;
+  if (uniform) {
+    hipLaunchKernelGGL((uniform_group_kernel<K, G>), dim3(L.n_wg), dim3(kSweepThreads), lds, stream,
+                       Wp, d_in, d_out, U, d_in, s0, c_codes, c_coef, c_E, c_score);
+  } else {
+    hipLaunchKernelGGL((bpdq_group_kernel<K, G>), dim3(L.n_wg), dim3(kSweepThreads), lds, stream,
+                       Wp, d_in, d_out, U, d_in, s0, T, p.alpha, c_codes, c_coef, c_E, c_score);
+  }
   BPDQ_LAUNCH_CHECK();
   hipLaunchKernelGGL((commit_group_kernel<K, G>), dim3(L.lde / kRowsPerWG), dim3(256), 0, stream,
-                     c_codes, c_coef, c_E, c_score, L.n_wg, p.refine_iters, grp_err + gi,
-                     grp_iter + gi, d_out, d_in, s0, b0, planes, coefs, W_hat, Eblk, L.lde);
+                     c_codes, c_coef, c_E, c_score, L.n_wg, T, grp_err + gi, grp_iter + gi, d_out,
+                     d_in, s0, b0, planes, coefs, W_hat, Eblk, L.lde);
   BPDQ_LAUNCH_CHECK();
   return 0;
 }
@@ -494,12 +688,17 @@ typedef int (*GroupLauncher)(hipStream_t, const float*, int, int, const float*, 
                              const bpdq_params&, const QuantLayout&, char*, uint32_t*, float*,
                              float*, double*, int*);
 
-// One translation unit per plane count instantiates the group kernels (they are large, fully
-// unrolled kernels; splitting them keeps the build parallel).
+// The group kernels are large, fully unrolled kernels: one translation unit per plane count
+// instantiates group sizes 32 / 64 / 128, and one more per plane count group size 256, which
+// keeps the build parallel.
 GroupLauncher pick_group_k1(int g);
 GroupLauncher pick_group_k2(int g);
 GroupLauncher pick_group_k3(int g);
 GroupLauncher pick_group_k4(int g);
+GroupLauncher group256_k1();
+GroupLauncher group256_k2();
+GroupLauncher group256_k3();
+GroupLauncher group256_k4();
 
 template <int K>
 static inline GroupLauncher pick_group_g(int g) {

@@ -79,18 +79,27 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint32_t* __restrict
 static int check_params(int d_out, int d_in, const bpdq_params* p) {
   if (!p) return 1;
   if (p->bits < 1 || p->bits > 4) return 1;
-  if (p->group != 32 && p->group != 64 && p->group != 128) return 1;
+  if (p->group != 32 && p->group != 64 && p->group != 128 && p->group != 256) return 1;
   if (d_in % p->group || d_in % 32) return 1;
   const int B = p->block > p->group ? p->block : p->group;
   if (p->block < 1 || B % p->group) return 1;
   if (p->refine_iters < 0 || p->refine_iters > 63) return 1;
   if (!(p->alpha >= 0.f)) return 1;
-  if (p->select_per_row != 0) return 1;
+  if (p->grid != BPDQ_GRID_VARIABLE && p->grid != BPDQ_GRID_UNIFORM) return 1;
   if (d_out <= 0 || d_in <= 0) return 1;
   return 0;
 }
 
 static GroupLauncher pick_group(int k, int g) {
+  if (g == 256) {
+    switch (k) {
+      case 1: return group256_k1();
+      case 2: return group256_k2();
+      case 3: return group256_k3();
+      case 4: return group256_k4();
+    }
+    return nullptr;
+  }
   switch (k) {
     case 1: return pick_group_k1(g);
     case 2: return pick_group_k2(g);

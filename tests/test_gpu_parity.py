@@ -192,6 +192,64 @@ def test_quantize_layer_stage_isolated(dev, bits, group, block, iters, d_out, d_
     assert np.all(it_g >= 0) and np.all(it_g <= iters)
 
 
+@pytest.mark.parametrize("bits,group,block,d_out,d_in", [
+    (2, 256, 128, 96, 512),        # g = 256 (the paper's W2-G256 setting), block widened to g
+    (3, 256, 256, 40, 256),
+    (4, 256, 256, 24, 512),
+])
+def test_quantize_layer_group_256(dev, bits, group, block, d_out, d_in):
+    print(f"quantize k={bits} g={group} {d_out}x{d_in}", flush=True)
+    wl, W, X = _problem("cfg1_tiny", d_out, d_in, 4 * d_in)
+    H = np.zeros((d_in, d_in))
+    orc.hessian_accumulate(X.numpy(), H)
+    Uref, dead, info = orc.prepare(H, wl.damp)
+    U32 = Uref.astype(np.float32)
+    Ht = np.linalg.inv(U32.astype(np.float64).T @ U32.astype(np.float64))
+    ref, out = _run_both(dev, wl, W, U32, dead, bits, group, block, 4)
+    _check_layer(ref, out, W, Ht, bits, group)
+
+
+@pytest.mark.parametrize("bits,group,block,d_out,d_in", [
+    (2, 64, 128, 200, 384), (3, 128, 128, 64, 256), (4, 32, 64, 33, 128), (2, 256, 256, 48, 512),
+])
+def test_uniform_grid_comparator(dev, bits, group, block, d_out, d_in):
+    """BPDQ_GRID_UNIFORM: the fixed-uniform-grid sweep (GPTQ on the min/max grid, App. A)
+    against the oracle's statement of it, both given the same fp32 U."""
+    print(f"uniform grid k={bits} g={group} {d_out}x{d_in}", flush=True)
+    wl, W, X = _problem("cfg2_qwen7b_attn", d_out, d_in, 4 * d_in)
+    H = np.zeros((d_in, d_in))
+    orc.hessian_accumulate(X.numpy(), H)
+    Uref, dead, info = orc.prepare(H, wl.damp)
+    U32 = Uref.astype(np.float32)
+    U64 = U32.astype(np.float64)
+    Ht = np.linalg.inv(U64.T @ U64)
+    ref = orc.quantize_layer(W.numpy(), U64, dead, bits, group, block, 0,
+                             group_fn=lambda T, UL: orc.uniform_frozen_group(T, UL, bits))
+    p = bq.make_params(bits, group, block, 5, wl.alpha, grid=bq.GRID_UNIFORM)
+    out = bq.bpdq_quantize_layer(W.to(dev), torch.from_numpy(U32).to(dev), None, p)
+    torch.cuda.synchronize()
+    code = orc.unpack_planes(out["planes"].cpu().numpy().view(np.uint32), d_in)
+    assert np.mean(code != ref["code"]) <= PLANE_TOL
+    Wn = W.numpy().astype(np.float64)
+    og = orc.layer_objective(Wn, out["W_hat"].cpu().numpy(), Ht)
+    orf = orc.layer_objective(Wn, ref["What"], Ht)
+    print(f"   codes differing {np.mean(code != ref['code']):.2e}, objective rel {abs(og - orf) / orf:.2e}", flush=True)
+    assert abs(og - orf) / orf <= OBJ_TOL
+    assert abs(float(out["grp_err"].sum().item()) - og) / og < 1e-3
+    assert bool((out["grp_iter"] == 0).all())
+    # coefficients are the uniform grid (lo, s, 2s, ...) and What is on that grid
+    cf = out["coefs"].cpu().numpy()
+    for i in range(2, bits + 1):
+        assert np.array_equal(cf[i], 2 * cf[i - 1])
+    assert np.allclose(cf[0], ref["coef"][0], rtol=1e-6, atol=1e-9)
+    # the paper's claim at layer level: the variable grid does better on the same inputs
+    pv = bq.make_params(bits, group, block, 5, wl.alpha)
+    outv = bq.bpdq_quantize_layer(W.to(dev), torch.from_numpy(U32).to(dev), None, pv)
+    ov = orc.layer_objective(Wn, outv["W_hat"].cpu().numpy(), Ht)
+    print(f"   objective variable grid / uniform grid = {ov / og:.3f}", flush=True)
+    assert ov < og
+
+
 def test_quantize_layer_heavy_tails_and_dead_channel(dev):
     print("quantize student-t + dead channel", flush=True)
     wl, W, X = _problem("cfg5_qwen72b_down", 96, 256, 1024)

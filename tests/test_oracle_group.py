@@ -275,3 +275,19 @@ def test_variable_grid_not_worse_than_uniform_per_group(k, seed):
     c = orc.fit_coefficients(u["code"], T, UL, k, alpha=0.0)
     E_var = orc.solve_right(T - orc.reconstruct(u["code"], c, k), UL)
     assert np.all(np.sum(E_var ** 2, axis=1) <= np.sum(u["E"] ** 2, axis=1) * (1 + 1e-12))
+
+
+def test_uniform_frozen_group_is_the_uniform_grid_sweep():
+    # the comparator entry point: same result as the plain uniform-grid GPTQ sweep
+    k, g = 3, 32
+    rng = np.random.default_rng(77)
+    UL = _local_factor(g, 17)
+    T = rng.standard_t(4, size=(30, g)) * 0.02
+    T[7] = 0.125                                   # a flat row
+    a = orc.uniform_frozen_group(T, UL, k, decision_dtype=None)
+    b = uni.uniform_group(T, UL, k)
+    assert np.array_equal(a["code"], b["code"])
+    assert np.allclose(a["coef"], b["coef"], rtol=1e-15)
+    assert np.allclose(a["What"], b["What"], rtol=1e-13, atol=1e-16)
+    assert np.allclose(a["E"], b["E"], rtol=1e-9, atol=1e-13)
+    assert np.all(a["code"][7] == 0)
