@@ -29,6 +29,10 @@ namespace bpdq {
 
 constexpr int kRowsPerWG = 16;
 constexpr int kSweepThreads = 256;
+// Two work-groups per CU (a sweeping one and one in the tail role) need the kernel within 256
+// registers per lane; the state of a g = 256 group does not fit that.
+template <int G>
+constexpr int kSweepWavesPerSimd = (G <= 128) ? 2 : 1;
 
 // ------------------------------------------------------------------ lane helpers -----------
 template <int CTRL>
@@ -362,6 +366,116 @@ __device__ __forceinline__ void level_table(const float (&c)[K + 1], float (&lv)
   }
 }
 
+// ------------------------------------------------------------------ pending updates --------
+// Error compensation of the columns not yet quantized (Eq. 4) is applied lazily, block by block
+// (App. B.3, tail form), and never on the critical path between two groups:
+//   * every committed E* is kept K-major in Eall[column][row] (leading dimension lde);
+//   * the group that starts at column s0 reads its target left-looking:
+//       t = W'[rows, s0:s0+g] - Eall[kp0:s0, rows]^T U[kp0:s0, s0:s0+g]
+//     where kp0 is the start of the previous block: W' itself holds the updates of all blocks
+//     before that one;
+//   * the update of block q-1 to the columns beyond block q is a GEMM that extra work-groups of
+//     the first group launch of block q perform (the "tail role"): it only needs E* committed
+//     before the launch and touches no column the launch's sweep reads, so it overlaps the
+//     latency-bound sweep instead of waiting between two of them.
+struct TailArgs {
+  const float* Et;   // Eall + k0 * lde
+  int Kd;            // depth of the update (columns of the finished block)
+  int k0;            // first column of the finished block (row of U)
+  float* Wp;         // working copy W'
+  int c_begin, c_end;  // columns [c_begin, c_end) of W' to update
+  int tiles_n;       // column tiles; 0 = no tail work in this launch
+  int first_wg;      // work-groups below this index sweep
+};
+
+// W'[:, c_begin:c_end] -= Et^T U[k0:k0+Kd, c_begin:c_end], one 128 x 128 tile per work-group
+__device__ __forceinline__ void tail_role(const TailArgs& ta, const float* __restrict__ U, int ldu,
+                                          int lde, int ldw, int d_out) {
+  const int t = blockIdx.x - ta.first_wg;
+  const int tm = t / ta.tiles_n, tn = t % ta.tiles_n;
+  TailGemm::Acc acc;
+  TailGemm::zero(acc);
+  TailGemm::run<0>(ta.Et, lde, tm * TailGemm::kTileM, lde, U + (long)ta.k0 * ldu, ldu,
+                   ta.c_begin + tn * TailGemm::kTileN, ta.c_end, 0, ta.Kd, acc);
+  const int r0 = tm * TailGemm::kTileM, c0 = ta.c_begin + tn * TailGemm::kTileN;
+  float* Wp = ta.Wp;
+  const int c_end = ta.c_end;
+  TailGemm::for_each(acc, [&](int row, int col, float v) {
+    const int r = r0 + row, c = c0 + col;
+    if (r < d_out && c < c_end) Wp[(long)r * ldw + c] -= v;
+  });
+}
+
+// sT[r][c] = sum_{k < Kp} Eall[kp0 + k][row0 + r] * U[kp0 + k][s0 + c]   (16 rows x G columns)
+// with v_mfma_f32_16x16x4_f32: the column blocks of 16 are dealt to the four wavefronts; operands
+// go straight from global memory to registers (lane l: A[l % 16][l / 16], B[l / 16][l % 16]),
+// the result (register r of lane l = D[4 (l / 16) + r][l % 16]) to LDS.  Kp % 32 == 0.
+template <int G>
+struct PendingTile {
+  static constexpr int kStride = G + 4;
+  static constexpr int kFloats = kRowsPerWG * kStride;
+};
+template <int G>
+__device__ __forceinline__ void pending_update_tile(const float* __restrict__ Eall, int lde,
+                                                    const float* __restrict__ U, int ldu, int kp0,
+                                                    int Kp, int row0, int s0, float* sT) {
+  typedef float f4 __attribute__((ext_vector_type(4)));
+  constexpr int NB = G / 16, BPW = (NB + 3) / 4;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int i = lane & 15, kq = lane >> 4;
+  f4 acc[BPW];
+#pragma unroll
+  for (int b = 0; b < BPW; ++b) acc[b] = f4{0.f, 0.f, 0.f, 0.f};
+  const float* ap = Eall + (long)(kp0 + kq) * lde + row0 + i;
+  const float* bp = U + (long)(kp0 + kq) * ldu + s0 + 16 * wave * BPW + i;
+  const bool active = wave * BPW < NB;          // g = 32: two blocks, wavefronts 2 and 3 idle
+  if (active) {
+    // kChunk MFMA steps (4 columns of E* each) per round trip to memory: all their operands are
+    // requested before the first one is used.  Kp % 32 == 0 (g >= 32 divides it).
+    constexpr int kChunk = (BPW <= 2) ? 16 : 8;
+    for (int k = 0; k < Kp; k += 4 * kChunk) {
+      float a[kChunk], bv[kChunk][BPW];
+#pragma unroll
+      for (int u = 0; u < kChunk; ++u) {
+        const bool in = k + 4 * u < Kp;
+        a[u] = in ? ap[(long)(k + 4 * u) * lde] : 0.f;
+#pragma unroll
+        for (int b = 0; b < BPW; ++b) bv[u][b] = in ? bp[(long)(k + 4 * u) * ldu + 16 * b] : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < kChunk; ++u)
+#pragma unroll
+        for (int b = 0; b < BPW; ++b)
+          acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u], bv[u][b], acc[b], 0, 0, 0);
+    }
+#pragma unroll
+    for (int b = 0; b < BPW; ++b)
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        sT[(4 * kq + r) * PendingTile<G>::kStride + 16 * (wave * BPW + b) + i] = acc[b][r];
+  }
+}
+
+// Group-start working weights of this lane's columns: W' minus the pending updates.
+template <int K, int G>
+__device__ __forceinline__ void load_group_target(RowState<K, G>& st, const float* __restrict__ Wp,
+                                                  int ldw, int rr, int s0, int lane16,
+                                                  const float* __restrict__ Eall, int lde,
+                                                  const float* __restrict__ U, int ldu, int kp0,
+                                                  float* sT) {
+  constexpr int CPL = G / 16;
+  const float* wrow = Wp + (long)rr * ldw + s0;
+#pragma unroll
+  for (int m = 0; m < CPL; ++m) st.t[m] = wrow[16 * m + lane16];
+  if (kp0 < s0) {                                   // uniform over the launch
+    pending_update_tile<G>(Eall, lde, U, ldu, kp0, s0 - kp0, blockIdx.x * kRowsPerWG, s0, sT);
+    __syncthreads();
+    const float* trow = sT + (threadIdx.x >> 4) * PendingTile<G>::kStride;
+#pragma unroll
+    for (int m = 0; m < CPL; ++m) st.t[m] -= trow[16 * m + lane16];
+  }
+}
+
 template <int K, int G>
 struct Candidates {          // per-iterate scratch in the workspace
   unsigned char* codes;      // [T+1][d_out][G]
@@ -404,27 +518,31 @@ __device__ __forceinline__ void store_candidate(const RowState<K, G>& st, const 
 // One group of g columns for 16 rows per work-group: initialisation, fit, T refinement
 // iterations; every iterate's (codes, coefficients, E', score) is kept for the selection.
 template <int K, int G>
-__global__ __launch_bounds__(kSweepThreads) void bpdq_group_kernel(
+__global__ __launch_bounds__(kSweepThreads, kSweepWavesPerSimd<G>) void bpdq_group_kernel(
     const float* __restrict__ Wp, int ldw, int d_out, const float* __restrict__ U, int ldu, int s0,
     int T, float alpha, unsigned char* __restrict__ cand_codes, float* __restrict__ cand_coef,
-    float* __restrict__ cand_E, double* __restrict__ cand_score) {
+    float* __restrict__ cand_E, double* __restrict__ cand_score, int n_wg,
+    const float* __restrict__ Eall, int lde, int kp0, TailArgs ta) {
+  if ((int)blockIdx.x >= ta.first_wg) {
+    tail_role(ta, U, ldu, lde, ldw, d_out);
+    return;
+  }
   constexpr int CPL = G / 16;
   extern __shared__ float lds[];
   float* sU = lds;                            // packed local factor, see SuLayout
   float* sInv = lds + SuLayout<G>::floats();          // 1 / U_ll
   double* sScore = reinterpret_cast<double*>(lds + SuLayout<G>::floats() + G);
+  float* sT = lds + SuLayout<G>::floats() + G + 2 * kRowsPerWG;   // pending-update tile
   const int tid = threadIdx.x;
   const int lane16 = tid & 15;
   stage_local_factor<G>(U, ldu, s0, sU, sInv);
-  __syncthreads();
 
   const int row = blockIdx.x * kRowsPerWG + (tid >> 4);
   const bool valid = row < d_out;
   const int rr = valid ? row : d_out - 1;
   RowState<K, G> st;
-  const float* wrow = Wp + (long)rr * ldw + s0;
-#pragma unroll
-  for (int m = 0; m < CPL; ++m) st.t[m] = wrow[16 * m + lane16];
+  load_group_target<K, G>(st, Wp, ldw, rr, s0, lane16, Eall, lde, U, ldu, kp0, sT);
+  __syncthreads();
 
   // ---- bit-plane initialisation (Sec. 3.2, Eq. 5): 8-bit affine RTN, keep the k MSB planes
   float lo = st.t[0], hi = st.t[0];
@@ -454,7 +572,6 @@ __global__ __launch_bounds__(kSweepThreads) void bpdq_group_kernel(
   using Seq = std::make_integer_sequence<int, G>;
   run_columns<K, G, kStepInit>(st, sU, sInv, lv, lane16, Seq{});
 
-  const int n_wg = gridDim.x;
   float c32[K + 1], Ep[CPL];
   double rs = fit_and_score<K, G>(st, (double)alpha, c32, Ep);
   store_candidate<K, G>(st, c32, Ep, rs, 0, row, valid, d_out, n_wg, cand_codes, cand_coef,
@@ -481,27 +598,31 @@ __global__ __launch_bounds__(kSweepThreads) void bpdq_group_kernel(
 // (lo, s, 2s, 4s, ...) -- the special case of Prop. 1.  One pass, no fit, no iteration: this is
 // GPTQ on the asymmetric min/max grid.  The result is stored as iterate 0.
 template <int K, int G>
-__global__ __launch_bounds__(kSweepThreads) void uniform_group_kernel(
+__global__ __launch_bounds__(kSweepThreads, kSweepWavesPerSimd<G>) void uniform_group_kernel(
     const float* __restrict__ Wp, int ldw, int d_out, const float* __restrict__ U, int ldu, int s0,
     unsigned char* __restrict__ cand_codes, float* __restrict__ cand_coef,
-    float* __restrict__ cand_E, double* __restrict__ cand_score) {
+    float* __restrict__ cand_E, double* __restrict__ cand_score, int n_wg,
+    const float* __restrict__ Eall, int lde, int kp0, TailArgs ta) {
+  if ((int)blockIdx.x >= ta.first_wg) {
+    tail_role(ta, U, ldu, lde, ldw, d_out);
+    return;
+  }
   constexpr int CPL = G / 16;
   extern __shared__ float lds[];
   float* sU = lds;
   float* sInv = lds + SuLayout<G>::floats();
   double* sScore = reinterpret_cast<double*>(lds + SuLayout<G>::floats() + G);
+  float* sT = lds + SuLayout<G>::floats() + G + 2 * kRowsPerWG;
   const int tid = threadIdx.x;
   const int lane16 = tid & 15;
   stage_local_factor<G>(U, ldu, s0, sU, sInv);
-  __syncthreads();
 
   const int row = blockIdx.x * kRowsPerWG + (tid >> 4);
   const bool valid = row < d_out;
   const int rr = valid ? row : d_out - 1;
   RowState<K, G> st;
-  const float* wrow = Wp + (long)rr * ldw + s0;
-#pragma unroll
-  for (int m = 0; m < CPL; ++m) st.t[m] = wrow[16 * m + lane16];
+  load_group_target<K, G>(st, Wp, ldw, rr, s0, lane16, Eall, lde, U, ldu, kp0, sT);
+  __syncthreads();
   float lo = st.t[0], hi = st.t[0];
 #pragma unroll
   for (int m = 1; m < CPL; ++m) {
@@ -532,7 +653,7 @@ __global__ __launch_bounds__(kSweepThreads) void uniform_group_kernel(
     sc += (double)Ep[m] * (double)Ep[m];
   }
   sc = row_sum_d(sc);
-  store_candidate<K, G>(st, c32, Ep, sc, 0, row, valid, d_out, gridDim.x, cand_codes, cand_coef,
+  store_candidate<K, G>(st, c32, Ep, sc, 0, row, valid, d_out, n_wg, cand_codes, cand_coef,
                         cand_E, cand_score, sScore, lane16);
 }
 
@@ -541,7 +662,7 @@ __global__ __launch_bounds__(kSweepThreads) void uniform_group_kernel(
 // the earliest minimum (Sec. 3.3: keep the iterate with the smallest ||E_group||_F^2), so all
 // work-groups agree bit for bit; work-group 0 publishes grp_iter / grp_err.  Then the kept
 // iterate is written out: packed planes (wave ballots), coefficients, What, and E* transposed
-// into the block's K-major error buffer Eblk[(s0 - b0) + j][row] (leading dimension lde).
+// into the K-major error buffer Eblk[(s0 - b0) + j][row] (leading dimension lde).
 template <int K, int G>
 __global__ __launch_bounds__(256) void commit_group_kernel(
     const unsigned char* __restrict__ cand_codes, const float* __restrict__ cand_coef,
@@ -626,7 +747,7 @@ __global__ __launch_bounds__(256) void commit_group_kernel(
 
 // ------------------------------------------------------------------ host side --------------
 struct QuantLayout {
-  size_t wp_off, eblk_off, codes_off, coef_off, e_off, score_off, total;
+  size_t wp_off, eall_off, codes_off, coef_off, e_off, score_off, total;
   int B, lde, n_wg;
 };
 
@@ -638,7 +759,7 @@ static inline QuantLayout quant_layout(int d_out, int d_in, const bpdq_params& p
   L.n_wg = bpdq_ceil_div(d_out, kRowsPerWG);
   size_t off = 0;
   L.wp_off = off;    off += bpdq_align_up((size_t)d_out * d_in * sizeof(float), 256);
-  L.eblk_off = off;  off += bpdq_align_up((size_t)L.B * L.lde * sizeof(float), 256);
+  L.eall_off = off;  off += bpdq_align_up((size_t)d_in * L.lde * sizeof(float), 256);
   L.codes_off = off; off += bpdq_align_up((size_t)(T + 1) * d_out * g, 256);
   L.coef_off = off;  off += bpdq_align_up((size_t)(T + 1) * d_out * (K + 1) * sizeof(float), 256);
   L.e_off = off;     off += bpdq_align_up((size_t)(T + 1) * d_out * g * sizeof(float), 256);
@@ -647,17 +768,20 @@ static inline QuantLayout quant_layout(int d_out, int d_in, const bpdq_params& p
   return L;
 }
 
+// One group: the sweep kernel (with the pending updates read left-looking from column kp0 on, and
+// the tail role `ta` for the previous block, see above), then selection + commit.
 template <int K, int G>
 static inline int launch_group(hipStream_t stream, const float* Wp, int d_out, int d_in, const float* U,
-                        int s0, int b0, const bpdq_params& p, const QuantLayout& L, char* base,
-                        uint32_t* planes, float* coefs, float* W_hat, double* grp_err,
+                        int s0, int kp0, TailArgs ta, const bpdq_params& p, const QuantLayout& L,
+                        char* base, uint32_t* planes, float* coefs, float* W_hat, double* grp_err,
                         int* grp_iter) {
   unsigned char* c_codes = reinterpret_cast<unsigned char*>(base + L.codes_off);
   float* c_coef = reinterpret_cast<float*>(base + L.coef_off);
   float* c_E = reinterpret_cast<float*>(base + L.e_off);
   double* c_score = reinterpret_cast<double*>(base + L.score_off);
-  float* Eblk = reinterpret_cast<float*>(base + L.eblk_off);
-  const size_t lds = (size_t)(SuLayout<G>::floats() + G) * sizeof(float) + kRowsPerWG * sizeof(double);
+  float* Eall = reinterpret_cast<float*>(base + L.eall_off);
+  size_t lds = (size_t)(SuLayout<G>::floats() + G + 2 * kRowsPerWG + PendingTile<G>::kFloats) * sizeof(float);
+  if (lds < TailGemm::kLdsBytes) lds = TailGemm::kLdsBytes;
   static bool attr_set = false;
   if (!attr_set) {
     BPDQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(bpdq_group_kernel<K, G>),
@@ -669,22 +793,27 @@ static inline int launch_group(hipStream_t stream, const float* Wp, int d_out, i
   const int gi = s0 / G;
   const bool uniform = (p.grid == BPDQ_GRID_UNIFORM);
   const int T = uniform ? 0 : p.refine_iters;
+  ta.first_wg = L.n_wg;
+  const int n_tail = ta.tiles_n > 0 ? bpdq_ceil_div(L.lde, TailGemm::kTileM) * ta.tiles_n : 0;
+  const dim3 grid(L.n_wg + n_tail);
   if (uniform) {
-    hipLaunchKernelGGL((uniform_group_kernel<K, G>), dim3(L.n_wg), dim3(kSweepThreads), lds, stream,
-                       Wp, d_in, d_out, U, d_in, s0, c_codes, c_coef, c_E, c_score);
+    hipLaunchKernelGGL((uniform_group_kernel<K, G>), grid, dim3(kSweepThreads), lds, stream,
+                       Wp, d_in, d_out, U, d_in, s0, c_codes, c_coef, c_E, c_score, L.n_wg, Eall,
+                       L.lde, kp0, ta);
   } else {
-    hipLaunchKernelGGL((bpdq_group_kernel<K, G>), dim3(L.n_wg), dim3(kSweepThreads), lds, stream,
-                       Wp, d_in, d_out, U, d_in, s0, T, p.alpha, c_codes, c_coef, c_E, c_score);
+    hipLaunchKernelGGL((bpdq_group_kernel<K, G>), grid, dim3(kSweepThreads), lds, stream,
+                       Wp, d_in, d_out, U, d_in, s0, T, p.alpha, c_codes, c_coef, c_E, c_score,
+                       L.n_wg, Eall, L.lde, kp0, ta);
   }
   BPDQ_LAUNCH_CHECK();
   hipLaunchKernelGGL((commit_group_kernel<K, G>), dim3(L.lde / kRowsPerWG), dim3(256), 0, stream,
                      c_codes, c_coef, c_E, c_score, L.n_wg, T, grp_err + gi, grp_iter + gi, d_out,
-                     d_in, s0, b0, planes, coefs, W_hat, Eblk, L.lde);
+                     d_in, s0, 0, planes, coefs, W_hat, Eall, L.lde);
   BPDQ_LAUNCH_CHECK();
   return 0;
 }
 
-typedef int (*GroupLauncher)(hipStream_t, const float*, int, int, const float*, int, int,
+typedef int (*GroupLauncher)(hipStream_t, const float*, int, int, const float*, int, int, TailArgs,
                              const bpdq_params&, const QuantLayout&, char*, uint32_t*, float*,
                              float*, double*, int*);
 

@@ -1,26 +1,9 @@
-// Steps 3-4 of the pass, host side: the loop over blocks and groups (paper Sec. 3.2, 3.3), the
-// lazy block-update GEMM (Eq. 4 applied to whole blocks; App. B.3 tail form) and the storage
-// helpers.  The per-group kernels live in group_sweep.h.
+// Steps 3-4 of the pass, host side: the loop over blocks and groups (paper Sec. 3.2, 3.3) with
+// the schedule of the lazy block updates (Eq. 4 applied to whole blocks; App. B.3 tail form) and
+// the storage helpers.  The per-group kernels live in group_sweep.h.
 #include "group_sweep.h"
 
 namespace bpdq {
-
-// W'[:, c_begin:c_end] -= Et^T * U[k0:k0+Kd, c_begin:c_end]   (Eq. 4 applied to a whole block:
-// the lazy update of the columns not yet quantized; also the rest-of-block update when g < B)
-__global__ __launch_bounds__(TailGemm::kThreads) void tail_update_kernel(
-    const float* __restrict__ Et, int lde, int Kd, const float* __restrict__ U, int ldu, int k0,
-    float* __restrict__ Wp, int ldw, int d_out, int c_begin, int c_end, int tiles_n) {
-  const int tm = blockIdx.x / tiles_n, tn = blockIdx.x % tiles_n;
-  TailGemm::Acc acc;
-  TailGemm::zero(acc);
-  TailGemm::run<0>(Et, lde, tm * TailGemm::kTileM, lde, U + (long)k0 * ldu, ldu,
-                       c_begin + tn * TailGemm::kTileN, c_end, 0, Kd, acc);
-  const int r0 = tm * TailGemm::kTileM, c0 = c_begin + tn * TailGemm::kTileN;
-  TailGemm::for_each(acc, [&](int row, int col, float v) {
-    const int r = r0 + row, c = c0 + col;
-    if (r < d_out && c < c_end) Wp[(long)r * ldw + c] -= v;
-  });
-}
 
 // working copy of W with dead input channels zeroed
 __global__ __launch_bounds__(256) void copy_in_kernel(const float* __restrict__ W, long n, int d_in,
@@ -109,24 +92,6 @@ static GroupLauncher pick_group(int k, int g) {
   return nullptr;
 }
 
-static int launch_tail_update(hipStream_t stream, const float* Et, int lde, int Kd, const float* U,
-                              int d_in, int k0, float* Wp, int d_out, int c_begin, int c_end) {
-  if (c_end <= c_begin) return 0;
-  static bool attr_set = false;
-  if (!attr_set) {
-    BPDQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(tail_update_kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     (int)TailGemm::kLdsBytes));
-    attr_set = true;
-  }
-  const int tiles_m = bpdq_ceil_div(lde, TailGemm::kTileM);
-  const int tiles_n = bpdq_ceil_div(c_end - c_begin, TailGemm::kTileN);
-  hipLaunchKernelGGL(tail_update_kernel, dim3(tiles_m * tiles_n), dim3(TailGemm::kThreads),
-                     TailGemm::kLdsBytes, stream, Et, lde, Kd, U, d_in, k0, Wp, d_in, d_out, c_begin, c_end, tiles_n);
-  BPDQ_LAUNCH_CHECK();
-  return 0;
-}
-
 }  // namespace bpdq
 
 using namespace bpdq;
@@ -157,7 +122,7 @@ extern "C" int bpdq_quantize_layer(const float* W, int d_out, int d_in, const fl
   if (ws_bytes < L.total) return -13;
   char* base = static_cast<char*>(ws);
   float* Wp = reinterpret_cast<float*>(base + L.wp_off);
-  float* Eblk = reinterpret_cast<float*>(base + L.eblk_off);
+  float* Eall = reinterpret_cast<float*>(base + L.eall_off);
   GroupLauncher group = pick_group(p->bits, p->group);
   if (!group) return -6;
 
@@ -166,21 +131,29 @@ extern "C" int bpdq_quantize_layer(const float* W, int d_out, int d_in, const fl
   hipLaunchKernelGGL(copy_in_kernel, dim3(grid), dim3(256), 0, stream, W, n, d_in, dead, Wp);
   BPDQ_LAUNCH_CHECK();
 
+  // Blocks of B columns, groups of g inside.  W' only ever receives whole-block updates, one
+  // block late: the first group launch of block q carries the update of block q-1 to the columns
+  // beyond block q (tail role), and every group of block q reads the updates of block q-1 and of
+  // the earlier groups of its own block left-looking from the committed E*.
   const int g = p->group, B = L.B;
   for (int b0 = 0; b0 < d_in; b0 += B) {
     const int b1 = b0 + B < d_in ? b0 + B : d_in;
+    const int kp0 = b0 > 0 ? b0 - B : 0;
     for (int s0 = b0; s0 < b1; s0 += g) {
-      int rc = group(stream, Wp, d_out, d_in, U, s0, b0, *p, L, base, planes, coefs, W_hat,
-                     grp_err, grp_iter);
-      if (rc) return rc;
-      // rest of this block (only when g < B): W'[:, s0+g:b1] -= E* U[s0:s0+g, s0+g:b1]
-      rc = launch_tail_update(stream, Eblk + (long)(s0 - b0) * L.lde, L.lde, g, U, d_in, s0, Wp,
-                              d_out, s0 + g, b1);
+      TailArgs ta{};
+      if (s0 == b0 && b0 > 0 && b1 < d_in) {
+        ta.Et = Eall + (long)kp0 * L.lde;
+        ta.Kd = B;
+        ta.k0 = kp0;
+        ta.Wp = Wp;
+        ta.c_begin = b1;
+        ta.c_end = d_in;
+        ta.tiles_n = bpdq_ceil_div(d_in - b1, TailGemm::kTileN);
+      }
+      const int rc = group(stream, Wp, d_out, d_in, U, s0, kp0, ta, *p, L, base, planes, coefs,
+                           W_hat, grp_err, grp_iter);
       if (rc) return rc;
     }
-    // lazy block update of every later column
-    const int rc = launch_tail_update(stream, Eblk, L.lde, b1 - b0, U, d_in, b0, Wp, d_out, b1, d_in);
-    if (rc) return rc;
   }
   return 0;
 }
