@@ -48,6 +48,13 @@ typedef struct bpdq_params {
                            lo + s*{0..2^k-1} per (row, group) from the group's min/max, one
                            sweep, no fit (GPTQ on a uniform grid); refine_iters and alpha are
                            ignored, the coefficients returned are (lo, s, 2s, ...).             */
+  int   coef_fp16;      /* storage precision of the coefficients (Table 1 counts 16 bits each).
+                           0: fp32 throughout.  1: every coefficient is rounded to IEEE half
+                           (nearest even) right after its fit, so the levels of the next bit-plane
+                           update, What, E*, the scores and the compensation all belong to the
+                           values that are stored; `coefs` still holds floats, each exactly a
+                           half (bpdq_coefs_to_fp16 is then lossless).  Magnitudes above 65504
+                           would become infinite: scale such a layer first.                    */
 } bpdq_params;
 
 /* Library version (major*10000 + minor*100 + patch). */
@@ -112,6 +119,16 @@ int bpdq_pack_planes(const unsigned char* codes, int d_out, int d_in, int bits,
 /* W_hat[r][c] = ((C_0 + b_1 C_1) + b_2 C_2) + ... evaluated in fp32 in this order. */
 int bpdq_dequant(const uint32_t* planes, const float* coefs, int d_out, int d_in, int bits,
                  int group, float* W_hat, void* stream);
+
+/* Storage format with 16-bit coefficients: k plane bits per weight plus (k+1) halves per
+ * (row, group), i.e. k + 16 (k+1) / g bits per weight (the BPW column of Table 1).
+ * bpdq_coefs_to_fp16: out[i] = half(coefs[i]), round to nearest even, n values (uint16 bit
+ * patterns).  bpdq_dequant_fp16: as bpdq_dequant with the coefficients read as halves; the sum
+ * is evaluated in fp32 in the same order, so for a layer quantized with coef_fp16 = 1 it
+ * reproduces that call's W_hat bit for bit. */
+int bpdq_coefs_to_fp16(const float* coefs, long n, uint16_t* out, void* stream);
+int bpdq_dequant_fp16(const uint32_t* planes, const uint16_t* coefs_h, int d_out, int d_in,
+                      int bits, int group, float* W_hat, void* stream);
 
 #ifdef __cplusplus
 }

@@ -48,7 +48,7 @@ from scipy.linalg import solve_triangular
 __all__ = [
     "hessian_accumulate", "prepare", "init_codes", "design_matrix", "fit_coefficients",
     "level_table", "nearest_level", "bitplane_sweep", "reconstruct", "solve_right",
-    "bpdq_group", "uniform_frozen_group", "quantize_layer", "pack_planes", "unpack_planes", "dequant",
+    "round_coefficients", "bpdq_group", "uniform_frozen_group", "quantize_layer", "pack_planes", "unpack_planes", "dequant",
     "layer_objective", "bits_per_weight",
 ]
 
@@ -145,6 +145,17 @@ def fit_coefficients(code, T, UL, k, alpha=1e-4):
     return np.linalg.solve(G, b[:, :, None])[:, :, 0]
 
 
+def round_coefficients(c, coef_dtype=None):
+    """Storage precision of the coefficients.  Table 1 counts 16 bits per coefficient; the
+    paper does not say when the rounding happens.  Reading taken: with `coef_dtype=np.float16`
+    every fitted coefficient is rounded (fp64 -> fp32 -> fp16, round to nearest even) right
+    after the fit, so that the levels of the next bit-plane update, What, the propagation
+    coordinates E and the score all belong to the values that are stored.  None = no rounding."""
+    if coef_dtype is None:
+        return c
+    return np.asarray(c).astype(np.float32).astype(coef_dtype).astype(np.float64)
+
+
 # --------------------------------------------------------------------------- #
 # Step 3c: bit-plane update  (Sec. 3.3 "Bit-plane Update", Eq. 7-8; Eq. 3-4)
 # --------------------------------------------------------------------------- #
@@ -211,7 +222,7 @@ def solve_right(R, UL):
 # Step 3 for one group: init, fit, iterate, keep the best iterate (Sec. 3.2, 3.3)
 # --------------------------------------------------------------------------- #
 def bpdq_group(T, UL, k, refine_iters, alpha=1e-4, select_per_row=False,
-               decision_dtype=np.float32, trace=None):
+               decision_dtype=np.float32, trace=None, coef_dtype=None):
     """Quantize one group given its group-start working block T (rows x g) and
     the local factor UL.  Returns dict(code, coef, What, E, score, it):
     E is the propagation coordinate block consistent with the returned What
@@ -220,7 +231,7 @@ def bpdq_group(T, UL, k, refine_iters, alpha=1e-4, select_per_row=False,
     T = np.asarray(T, dtype=np.float64)
     rows, g = T.shape
     code = init_codes(T, k, decision_dtype)
-    c = fit_coefficients(code, T, UL, k, alpha)
+    c = round_coefficients(fit_coefficients(code, T, UL, k, alpha), coef_dtype)
     What = reconstruct(code, c, k)
     E = solve_right(T - What, UL)
     rs = np.sum(E * E, axis=1)
@@ -230,7 +241,7 @@ def bpdq_group(T, UL, k, refine_iters, alpha=1e-4, select_per_row=False,
         trace.append(dict(it=0, score=float(rs.sum()), rowscore=rs.copy()))
     for t in range(1, refine_iters + 1):
         code_t, What_old, E_t = bitplane_sweep(T, UL, c, k, decision_dtype)
-        c = fit_coefficients(code_t, T, UL, k, alpha)                 # refit, Sec. 3.3
+        c = round_coefficients(fit_coefficients(code_t, T, UL, k, alpha), coef_dtype)  # refit, Sec. 3.3
         What_new = reconstruct(code_t, c, k)
         dE = solve_right(What_old - What_new, UL)                     # Eq. 9
         Ep = E_t + dE
@@ -252,7 +263,7 @@ def bpdq_group(T, UL, k, refine_iters, alpha=1e-4, select_per_row=False,
     return best
 
 
-def uniform_frozen_group(T, UL, k, decision_dtype=np.float32):
+def uniform_frozen_group(T, UL, k, decision_dtype=np.float32, coef_dtype=None):
     """The fixed uniform grid written as a variable grid (App. A, Prop. 1): coefficients frozen
     to (lo, s, 2s, 4s, ...), s = (hi - lo) / (2^k - 1) from the group-start block's per-row
     min / max (a flat row gets s = 1), one bit-plane update pass, no fit, no iteration.  This is
@@ -264,6 +275,7 @@ def uniform_frozen_group(T, UL, k, decision_dtype=np.float32):
     s = (hi - lo) / float((1 << k) - 1)
     s = np.where(s == 0.0, 1.0, s)
     c = np.stack([lo] + [s * (1 << i) for i in range(k)], axis=1)
+    c = round_coefficients(c, coef_dtype)
     code, What, E = bitplane_sweep(T, UL, c, k, decision_dtype)
     return dict(code=code, coef=c, What=What, E=E, it=np.zeros(T.shape[0], dtype=np.int32))
 
@@ -272,7 +284,8 @@ def uniform_frozen_group(T, UL, k, decision_dtype=np.float32):
 # Steps 3-4 for a layer: groups in GPTQ order with lazy block updates
 # --------------------------------------------------------------------------- #
 def quantize_layer(W, U, dead, bits, group, block, refine_iters, alpha=1e-4,
-                   select_per_row=False, decision_dtype=np.float32, group_fn=None, progress=None):
+                   select_per_row=False, decision_dtype=np.float32, group_fn=None, progress=None,
+                   coef_dtype=None):
     """Sweep the columns of W block by block (Sec. 3.1 compensation; App. B.3 tail
     form).  Returns dict with
       code   uint8  (d_out x d_in)     plane bits, bit (i-1) = B_i
@@ -305,7 +318,8 @@ def quantize_layer(W, U, dead, bits, group, block, refine_iters, alpha=1e-4,
     grp_iter = np.zeros((d_out, ngrp) if select_per_row else ngrp, dtype=np.int32)
     if group_fn is None:
         def group_fn(T, UL):
-            return bpdq_group(T, UL, k, refine_iters, alpha, select_per_row, decision_dtype)
+            return bpdq_group(T, UL, k, refine_iters, alpha, select_per_row, decision_dtype,
+                              coef_dtype=coef_dtype)
     for b0 in range(0, d_in, B):
         b1 = min(b0 + B, d_in)
         for s in range(b0, b1, g):

@@ -20,14 +20,14 @@ EXPORTS = [
     "bpdq_hessian_workspace_bytes", "bpdq_hessian_accumulate",
     "bpdq_prepare_workspace_bytes", "bpdq_prepare",
     "bpdq_quantize_workspace_bytes", "bpdq_quantize_layer",
-    "bpdq_pack_planes", "bpdq_dequant",
+    "bpdq_pack_planes", "bpdq_dequant", "bpdq_coefs_to_fp16", "bpdq_dequant_fp16",
 ]
 
 
 class BpdqParams(ctypes.Structure):
     _fields_ = [("bits", ctypes.c_int), ("group", ctypes.c_int), ("block", ctypes.c_int),
                 ("refine_iters", ctypes.c_int), ("alpha", ctypes.c_float),
-                ("grid", ctypes.c_int)]
+                ("grid", ctypes.c_int), ("coef_fp16", ctypes.c_int)]
 
 
 class BpdqError(RuntimeError):
@@ -63,6 +63,10 @@ def load():
     lib.bpdq_pack_planes.argtypes = [vp, ci, ci, ci, vp, vp]
     lib.bpdq_dequant.restype = ci
     lib.bpdq_dequant.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp]
+    lib.bpdq_dequant_fp16.restype = ci
+    lib.bpdq_dequant_fp16.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp]
+    lib.bpdq_coefs_to_fp16.restype = ci
+    lib.bpdq_coefs_to_fp16.argtypes = [vp, ctypes.c_long, vp, vp]
     _lib = lib
     return lib
 
@@ -141,8 +145,9 @@ def bpdq_prepare(H, damp=0.01, U=None, ws=None):
 GRID_VARIABLE, GRID_UNIFORM = 0, 1
 
 
-def make_params(bits, group, block, refine_iters, alpha=1e-4, grid=GRID_VARIABLE) -> BpdqParams:
-    return BpdqParams(bits, group, block, refine_iters, alpha, grid)
+def make_params(bits, group, block, refine_iters, alpha=1e-4, grid=GRID_VARIABLE,
+                coef_fp16=False) -> BpdqParams:
+    return BpdqParams(bits, group, block, refine_iters, alpha, grid, int(bool(coef_fp16)))
 
 
 def bpdq_quantize_workspace_bytes(d_out, d_in, params: BpdqParams) -> int:
@@ -197,4 +202,26 @@ def bpdq_dequant(planes, coefs, group):
     W_hat = torch.empty((d_out, d_in), dtype=torch.float32, device=planes.device)
     _check(lib.bpdq_dequant(_ptr(planes), _ptr(coefs), d_out, d_in, bits, group, _ptr(W_hat),
                             _stream()), "bpdq_dequant")
+    return W_hat
+
+
+def bpdq_coefs_to_fp16(coefs):
+    """Half-precision copy of the coefficients (same shape, torch.float16)."""
+    lib = load()
+    _dev(coefs, torch.float32, "coefs")
+    out = torch.empty(coefs.shape, dtype=torch.float16, device=coefs.device)
+    _check(lib.bpdq_coefs_to_fp16(_ptr(coefs), coefs.numel(), _ptr(out), _stream()),
+           "bpdq_coefs_to_fp16")
+    return out
+
+
+def bpdq_dequant_fp16(planes, coefs_h, group):
+    lib = load()
+    _dev(planes, torch.int32, "planes")
+    _dev(coefs_h, torch.float16, "coefs_h")
+    bits, d_out, nw = planes.shape
+    d_in = nw * 32
+    W_hat = torch.empty((d_out, d_in), dtype=torch.float32, device=planes.device)
+    _check(lib.bpdq_dequant_fp16(_ptr(planes), _ptr(coefs_h), d_out, d_in, bits, group, _ptr(W_hat),
+                                 _stream()), "bpdq_dequant_fp16")
     return W_hat

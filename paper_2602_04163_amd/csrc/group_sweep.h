@@ -282,9 +282,15 @@ __device__ __forceinline__ void stage_local_factor(const float* __restrict__ U, 
   }
 }
 
+// Storage precision of a coefficient: IEEE half (nearest even) when the layer is stored with
+// 16-bit coefficients (Table 1), so that everything computed from it belongs to the stored value.
+__device__ __forceinline__ float store_precision(float c, int coef_fp16) {
+  return coef_fp16 ? (float)(_Float16)c : c;
+}
+
 // Coefficient fit (Eq. 6) from the solved vectors; returns c (fp32) and the row's ||E'||^2.
 template <int K, int G>
-__device__ __forceinline__ double fit_and_score(const RowState<K, G>& st, double alpha,
+__device__ __forceinline__ double fit_and_score(const RowState<K, G>& st, double alpha, int coef_fp16,
                                                 float (&c32)[K + 1], float (&Ep)[G / 16]) {
   constexpr int CPL = G / 16, N = K + 1;
   double Gm[N][N], r[N];
@@ -340,7 +346,7 @@ __device__ __forceinline__ double fit_and_score(const RowState<K, G>& st, double
     c[a] = s / Gm[a][a];
   }
 #pragma unroll
-  for (int a = 0; a < N; ++a) c32[a] = (float)c[a];
+  for (int a = 0; a < N; ++a) c32[a] = store_precision((float)c[a], coef_fp16);
   double sc = 0.0;
 #pragma unroll
   for (int m = 0; m < CPL; ++m) {
@@ -520,7 +526,8 @@ __device__ __forceinline__ void store_candidate(const RowState<K, G>& st, const 
 template <int K, int G>
 __global__ __launch_bounds__(kSweepThreads, kSweepWavesPerSimd<G>) void bpdq_group_kernel(
     const float* __restrict__ Wp, int ldw, int d_out, const float* __restrict__ U, int ldu, int s0,
-    int T, float alpha, unsigned char* __restrict__ cand_codes, float* __restrict__ cand_coef,
+    int T, float alpha, int coef_fp16, unsigned char* __restrict__ cand_codes,
+    float* __restrict__ cand_coef,
     float* __restrict__ cand_E, double* __restrict__ cand_score, int n_wg,
     const float* __restrict__ Eall, int lde, int kp0, TailArgs ta) {
   if ((int)blockIdx.x >= ta.first_wg) {
@@ -573,7 +580,7 @@ __global__ __launch_bounds__(kSweepThreads, kSweepWavesPerSimd<G>) void bpdq_gro
   run_columns<K, G, kStepInit>(st, sU, sInv, lv, lane16, Seq{});
 
   float c32[K + 1], Ep[CPL];
-  double rs = fit_and_score<K, G>(st, (double)alpha, c32, Ep);
+  double rs = fit_and_score<K, G>(st, (double)alpha, coef_fp16, c32, Ep);
   store_candidate<K, G>(st, c32, Ep, rs, 0, row, valid, d_out, n_wg, cand_codes, cand_coef,
                         cand_E, cand_score, sScore, lane16);
 
@@ -587,7 +594,7 @@ __global__ __launch_bounds__(kSweepThreads, kSweepWavesPerSimd<G>) void bpdq_gro
       for (int i = 0; i < K; ++i) st.P[i][m] = 0.f;
     }
     run_columns<K, G, kStepSweep>(st, sU, sInv, lv, lane16, Seq{});
-    rs = fit_and_score<K, G>(st, (double)alpha, c32, Ep);
+    rs = fit_and_score<K, G>(st, (double)alpha, coef_fp16, c32, Ep);
     store_candidate<K, G>(st, c32, Ep, rs, it, row, valid, d_out, n_wg, cand_codes, cand_coef,
                           cand_E, cand_score, sScore, lane16);
   }
@@ -600,7 +607,7 @@ __global__ __launch_bounds__(kSweepThreads, kSweepWavesPerSimd<G>) void bpdq_gro
 template <int K, int G>
 __global__ __launch_bounds__(kSweepThreads, kSweepWavesPerSimd<G>) void uniform_group_kernel(
     const float* __restrict__ Wp, int ldw, int d_out, const float* __restrict__ U, int ldu, int s0,
-    unsigned char* __restrict__ cand_codes, float* __restrict__ cand_coef,
+    int coef_fp16, unsigned char* __restrict__ cand_codes, float* __restrict__ cand_coef,
     float* __restrict__ cand_E, double* __restrict__ cand_score, int n_wg,
     const float* __restrict__ Eall, int lde, int kp0, TailArgs ta) {
   if ((int)blockIdx.x >= ta.first_wg) {
@@ -634,9 +641,9 @@ __global__ __launch_bounds__(kSweepThreads, kSweepWavesPerSimd<G>) void uniform_
   float step = (hi - lo) / (float)((1 << K) - 1);
   if (step == 0.f) step = 1.0f;                 // flat row: every weight takes code 0
   float c32[K + 1], lv[1 << K], Ep[CPL];
-  c32[0] = lo;
+  c32[0] = store_precision(lo, coef_fp16);
 #pragma unroll
-  for (int i = 0; i < K; ++i) c32[i + 1] = step * (float)(1 << i);
+  for (int i = 0; i < K; ++i) c32[i + 1] = store_precision(step * (float)(1 << i), coef_fp16);
   level_table<K>(c32, lv);
 #pragma unroll
   for (int m = 0; m < CPL; ++m) {
@@ -798,11 +805,11 @@ static inline int launch_group(hipStream_t stream, const float* Wp, int d_out, i
   const dim3 grid(L.n_wg + n_tail);
   if (uniform) {
     hipLaunchKernelGGL((uniform_group_kernel<K, G>), grid, dim3(kSweepThreads), lds, stream,
-                       Wp, d_in, d_out, U, d_in, s0, c_codes, c_coef, c_E, c_score, L.n_wg, Eall,
+                       Wp, d_in, d_out, U, d_in, s0, p.coef_fp16, c_codes, c_coef, c_E, c_score, L.n_wg, Eall,
                        L.lde, kp0, ta);
   } else {
     hipLaunchKernelGGL((bpdq_group_kernel<K, G>), grid, dim3(kSweepThreads), lds, stream,
-                       Wp, d_in, d_out, U, d_in, s0, T, p.alpha, c_codes, c_coef, c_E, c_score,
+                       Wp, d_in, d_out, U, d_in, s0, T, p.alpha, p.coef_fp16, c_codes, c_coef, c_E, c_score,
                        L.n_wg, Eall, L.lde, kp0, ta);
   }
   BPDQ_LAUNCH_CHECK();

@@ -40,8 +40,13 @@ __global__ __launch_bounds__(256) void pack_planes_kernel(const unsigned char* _
   }
 }
 
+__device__ __forceinline__ float coef_value(float c) { return c; }
+__device__ __forceinline__ float coef_value(_Float16 c) { return (float)c; }
+
+// Eq. 1 from the packed format, ((C_0 + b_1 C_1) + b_2 C_2) + ... in fp32; CT = float or half
+template <typename CT>
 __global__ __launch_bounds__(256) void dequant_kernel(const uint32_t* __restrict__ planes,
-                                                      const float* __restrict__ coefs, int d_out,
+                                                      const CT* __restrict__ coefs, int d_out,
                                                       int d_in, int bits, int group,
                                                       float* __restrict__ W_hat) {
   const int n_word = d_in / 32, n_grp = d_in / group;
@@ -49,13 +54,19 @@ __global__ __launch_bounds__(256) void dequant_kernel(const uint32_t* __restrict
   for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < n; e += (long)gridDim.x * 256) {
     const int r = (int)(e / d_in), c = (int)(e % d_in);
     const int gi = c / group;
-    float v = coefs[(long)r * n_grp + gi];
+    float v = coef_value(coefs[(long)r * n_grp + gi]);
     for (int i = 0; i < bits; ++i) {
       const uint32_t w = planes[((long)i * d_out + r) * n_word + c / 32];
-      if ((w >> (c & 31)) & 1u) v = v + coefs[((long)(i + 1) * d_out + r) * n_grp + gi];
+      if ((w >> (c & 31)) & 1u) v = v + coef_value(coefs[((long)(i + 1) * d_out + r) * n_grp + gi]);
     }
     W_hat[e] = v;
   }
+}
+
+__global__ __launch_bounds__(256) void coefs_to_fp16_kernel(const float* __restrict__ coefs, long n,
+                                                            _Float16* __restrict__ out) {
+  for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < n; e += (long)gridDim.x * 256)
+    out[e] = (_Float16)coefs[e];                 // v_cvt_f16_f32: round to nearest even
 }
 
 // ------------------------------------------------------------------ host side --------------
@@ -69,6 +80,7 @@ static int check_params(int d_out, int d_in, const bpdq_params* p) {
   if (p->refine_iters < 0 || p->refine_iters > 63) return 1;
   if (!(p->alpha >= 0.f)) return 1;
   if (p->grid != BPDQ_GRID_VARIABLE && p->grid != BPDQ_GRID_UNIFORM) return 1;
+  if (p->coef_fp16 != 0 && p->coef_fp16 != 1) return 1;
   if (d_out <= 0 || d_in <= 0) return 1;
   return 0;
 }
@@ -173,9 +185,8 @@ extern "C" int bpdq_pack_planes(const unsigned char* codes, int d_out, int d_in,
   return 0;
 }
 
-extern "C" int bpdq_dequant(const uint32_t* planes, const float* coefs, int d_out, int d_in,
-                            int bits, int group, float* W_hat, void* stream_) {
-  hipStream_t stream = static_cast<hipStream_t>(stream_);
+static int launch_dequant(const uint32_t* planes, const void* coefs, bool half, int d_out, int d_in,
+                          int bits, int group, float* W_hat, hipStream_t stream) {
   if (!planes) return -1;
   if (!coefs) return -2;
   if (d_out <= 0) return -3;
@@ -185,8 +196,39 @@ extern "C" int bpdq_dequant(const uint32_t* planes, const float* coefs, int d_ou
   if (!W_hat) return -7;
   const long n = (long)d_out * d_in;
   const int grid = (int)((n + 255) / 256 < 65536 ? (n + 255) / 256 : 65536);
-  hipLaunchKernelGGL(dequant_kernel, dim3(grid), dim3(256), 0, stream, planes, coefs, d_out, d_in,
-                     bits, group, W_hat);
+  if (half) {
+    hipLaunchKernelGGL(dequant_kernel<_Float16>, dim3(grid), dim3(256), 0, stream, planes,
+                       static_cast<const _Float16*>(coefs), d_out, d_in, bits, group, W_hat);
+  } else {
+    hipLaunchKernelGGL(dequant_kernel<float>, dim3(grid), dim3(256), 0, stream, planes,
+                       static_cast<const float*>(coefs), d_out, d_in, bits, group, W_hat);
+  }
+  BPDQ_LAUNCH_CHECK();
+  return 0;
+}
+
+extern "C" int bpdq_dequant(const uint32_t* planes, const float* coefs, int d_out, int d_in,
+                            int bits, int group, float* W_hat, void* stream_) {
+  return launch_dequant(planes, coefs, false, d_out, d_in, bits, group, W_hat,
+                        static_cast<hipStream_t>(stream_));
+}
+
+extern "C" int bpdq_dequant_fp16(const uint32_t* planes, const uint16_t* coefs_h, int d_out,
+                                 int d_in, int bits, int group, float* W_hat, void* stream_) {
+  if (coefs_h && (reinterpret_cast<uintptr_t>(coefs_h) & 1)) return -2;
+  return launch_dequant(planes, coefs_h, true, d_out, d_in, bits, group, W_hat,
+                        static_cast<hipStream_t>(stream_));
+}
+
+extern "C" int bpdq_coefs_to_fp16(const float* coefs, long n, uint16_t* out, void* stream_) {
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  if (n < 0) return -2;
+  if (n == 0) return 0;
+  if (!coefs) return -1;
+  if (!out || (reinterpret_cast<uintptr_t>(out) & 1)) return -3;
+  const int grid = (int)((n + 255) / 256 < 65536 ? (n + 255) / 256 : 65536);
+  hipLaunchKernelGGL(coefs_to_fp16_kernel, dim3(grid), dim3(256), 0, stream, coefs, n,
+                     reinterpret_cast<_Float16*>(out));
   BPDQ_LAUNCH_CHECK();
   return 0;
 }

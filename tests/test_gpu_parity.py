@@ -120,11 +120,12 @@ def test_prepare_dead_channel_aliasing_and_failure(dev):
 
 
 # ------------------------------------------------------------------ steps 3-4: the sweep
-def _run_both(dev, wl, W, U32, dead, bits, group, block, iters):
+def _run_both(dev, wl, W, U32, dead, bits, group, block, iters, coef_fp16=False):
     """Stage-isolated: both sides get the same fp32 U."""
     ref = orc.quantize_layer(W.numpy(), U32.astype(np.float64), dead, bits, group, block, iters,
-                             alpha=float(np.float32(wl.alpha)))
-    p = bq.make_params(bits, group, block, iters, wl.alpha)
+                             alpha=float(np.float32(wl.alpha)),
+                             coef_dtype=np.float16 if coef_fp16 else None)
+    p = bq.make_params(bits, group, block, iters, wl.alpha, coef_fp16=coef_fp16)
     dead_t = None if dead is None else torch.from_numpy(dead.astype(np.uint8)).to(dev)
     out = bq.bpdq_quantize_layer(W.to(dev), torch.from_numpy(U32).to(dev), dead_t, p)
     torch.cuda.synchronize()
@@ -207,6 +208,61 @@ def test_quantize_layer_group_256(dev, bits, group, block, d_out, d_in):
     Ht = np.linalg.inv(U32.astype(np.float64).T @ U32.astype(np.float64))
     ref, out = _run_both(dev, wl, W, U32, dead, bits, group, block, 4)
     _check_layer(ref, out, W, Ht, bits, group)
+
+
+@pytest.mark.parametrize("bits,group,block,iters,d_out,d_in", [
+    (2, 128, 128, 5, 200, 384),
+    (3, 64, 128, 4, 72, 320),
+    (4, 32, 64, 2, 33, 128),
+    (2, 256, 256, 3, 40, 512),
+])
+def test_quantize_layer_fp16_coefficient_storage(dev, bits, group, block, iters, d_out, d_in):
+    """coef_fp16 = 1: coefficients rounded to half right after every fit (the storage precision
+    Table 1 counts).  Same parity bar as the fp32 path, against the oracle with the same reading;
+    the stored format (packed planes + halves) must reproduce W_hat bit for bit, and its size is
+    the closed form k + 16 (k+1) / g bits per weight."""
+    print(f"fp16 storage k={bits} g={group} B={block} T={iters} {d_out}x{d_in}", flush=True)
+    wl, W, X = _problem("cfg1_tiny", d_out, d_in, 4 * d_in)
+    H = np.zeros((d_in, d_in))
+    orc.hessian_accumulate(X.numpy(), H)
+    Uref, dead, info = orc.prepare(H, wl.damp)
+    U32 = Uref.astype(np.float32)
+    Ht = np.linalg.inv(U32.astype(np.float64).T @ U32.astype(np.float64))
+    ref, out = _run_both(dev, wl, W, U32, dead, bits, group, block, iters, coef_fp16=True)
+    _check_layer(ref, out, W, Ht, bits, group)
+    coefs = out["coefs"]
+    ch = bq.bpdq_coefs_to_fp16(coefs)
+    assert torch.equal(ch.float(), coefs)                      # every coefficient is a half
+    assert np.array_equal(ch.cpu().numpy(), coefs.cpu().numpy().astype(np.float16))
+    Wd = bq.bpdq_dequant_fp16(out["planes"], ch, group)
+    assert torch.equal(Wd, out["W_hat"])                       # stored format == W_hat
+    stored_bits = 8 * (out["planes"].numel() * 4 + ch.numel() * 2)
+    assert stored_bits / (d_out * d_in) == orc.bits_per_weight(bits, group)
+    # objective re-measured after rounding: rounding in the pass vs rounding afterwards vs fp32
+    Wn = W.numpy().astype(np.float64)
+    p32 = bq.make_params(bits, group, block, iters, wl.alpha)
+    out32 = bq.bpdq_quantize_layer(W.to(dev), torch.from_numpy(U32).to(dev), None, p32)
+    post = bq.bpdq_dequant_fp16(out32["planes"], bq.bpdq_coefs_to_fp16(out32["coefs"]), group)
+    o32 = orc.layer_objective(Wn, out32["W_hat"].cpu().numpy(), Ht)
+    o16 = orc.layer_objective(Wn, out["W_hat"].cpu().numpy(), Ht)
+    opost = orc.layer_objective(Wn, post.cpu().numpy(), Ht)
+    print(f"   objective fp32 {o32:.6e}; fp16 in the pass {o16 / o32:.5f}x; "
+          f"fp16 afterwards {opost / o32:.5f}x", flush=True)
+    assert abs(o16 / o32 - 1) < 2e-2 and abs(opost / o32 - 1) < 2e-2
+    # the pass's own scores describe the stored layer (App. B.2) only when it rounds itself
+    assert abs(float(out["grp_err"].sum().item()) - o16) / o16 < 1e-3
+
+
+def test_coefs_to_fp16_rounding_and_errors(dev):
+    print("coefs_to_fp16 rounding", flush=True)
+    rng = np.random.default_rng(11)
+    x = np.concatenate([rng.standard_normal(5000).astype(np.float32) * 0.05,
+                        np.float32([0.0, -0.0, 1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, 65504.0,
+                                    6e-8, 3e-8, -2.5e-5, 1e-7])])
+    got = bq.bpdq_coefs_to_fp16(torch.from_numpy(x).to(dev)).cpu().numpy()
+    assert np.array_equal(got.view(np.uint16), x.astype(np.float16).view(np.uint16))
+    empty = bq.bpdq_coefs_to_fp16(torch.empty(0, dtype=torch.float32, device=dev))
+    assert empty.numel() == 0
 
 
 @pytest.mark.parametrize("bits,group,block,d_out,d_in", [

@@ -22,7 +22,7 @@ def lib():
 def _declared():
     text = open(os.path.join(ROOT, "include", "bpdq.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(bpdq_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(bpdq_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported(lib):
@@ -49,6 +49,10 @@ def test_size_queries(lib):
     assert binding.bpdq_quantize_workspace_bytes(3584, 3584, bad) == 0
     bad = binding.make_params(2, 128, 128, 5, grid=7)
     assert binding.bpdq_quantize_workspace_bytes(3584, 3584, bad) == 0
+    bad = binding.make_params(2, 128, 128, 5)
+    bad.coef_fp16 = 2
+    assert binding.bpdq_quantize_workspace_bytes(3584, 3584, bad) == 0
+    assert binding.bpdq_quantize_workspace_bytes(3584, 3584, binding.make_params(2, 128, 128, 5, coef_fp16=True)) == need
     assert binding.bpdq_quantize_workspace_bytes(8192, 8192, binding.make_params(2, 256, 128, 10)) > 0
     assert binding.bpdq_prepare_workspace_bytes(3584) >= 3584 * 3584 * 8
     assert binding.bpdq_hessian_workspace_bytes(0, 3584) == 0
@@ -63,3 +67,6 @@ def test_argument_errors_are_reported_without_a_gpu(lib):
     assert lib.bpdq_prepare(None, 64, 0.01, None, None, None, None, 0, None) == -1
     assert lib.bpdq_pack_planes(None, 4, 64, 2, None, None) == -1
     assert lib.bpdq_dequant(None, None, 4, 64, 2, 32, None, None) == -1
+    assert lib.bpdq_dequant_fp16(None, None, 4, 64, 2, 32, None, None) == -1
+    assert lib.bpdq_coefs_to_fp16(None, 4, None, None) == -1
+    assert lib.bpdq_coefs_to_fp16(None, 0, None, None) == 0       # nothing to convert
