@@ -7,8 +7,9 @@
 // inverse (2/3 d^3 flops) and Ht^-1 is never formed.  Everything runs in fp64 inside the
 // workspace; the result is rounded to fp32 once, on output.
 //
-//   factor : right-looking over 64-column panels from the right: every panel work-group factors
-//            the diagonal block in registers and solves its 64 rows of R12 R22^T = A12.  The
+//   factor : right-looking over 64-column panels from the right, two panels per launch: every
+//            panel work-group factors the diagonal blocks in registers and solves its 64 rows
+//            of R12 R22^T = A12.  The
 //            trailing update A11 -= R12 R12^T (fp64 MFMA, upper 64 x 64 tiles) is two-level:
 //            after each panel only inside the current 512-column outer panel, and once per
 //            outer panel, with K = 512, on everything to its left.
@@ -73,45 +74,43 @@ __device__ __forceinline__ double fast_rcp(double x) {
   return r;
 }
 
-// Panel step of the reversed Cholesky, one work-group (256 threads) per 64 rows of the panel.
-//   (1) every work-group factors the 64 x 64 diagonal block D = R R^T (R upper, columns taken
-//       from the last to the first) for itself: thread (ty, tx) keeps the 4 x 4 sub-block
-//       rows 4ty.., cols 4tx.. in registers; per column one LDS broadcast of the current column,
-//       one barrier, one reciprocal and a rank-1 update  a -= col col^T / pivot.
-//   (2) rows [64 b, 64 b + 64) of the panel above the block: X R^T = A12 solved by substitution,
-//       one thread per row, the row held in registers.
-// Work-group 0 also writes R of the diagonal block to Rdiag (NB x NB, row-major, zero below the
-// diagonal, identity-padded) and reports a non-positive pivot.
-// Launch with max(p, 1) work-groups, p = number of 64-row blocks above the diagonal block.
-__global__ __launch_bounds__(256) void panel_factor_kernel(double* __restrict__ A, int d, int p0,
-                                                           int nb, int n_above,
-                                                           double* __restrict__ Rdiag, int* info) {
-  __shared__ double sR[NB][NB + 1];     // R (upper) of the diagonal block
-  __shared__ double sA[NB][NB + 1];     // panel tile of this work-group
-  __shared__ double col[2][NB];
-  __shared__ double sInvD[NB];
-  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
-
-  double a[4][4];
+// A 64 x 64 tile of doubles moves between global memory and LDS through registers, 16 elements
+// per thread of 256 (element e = tid + 256 t -> row e / 64, column e % 64).  All 16 loads of a
+// thread are issued before the first is used: a rolled loop would wait for memory 16 times.
+// ok(i, j): is the element read (else 0);  idx(i, j): its offset from `base`, which must itself
+// be a valid address (masked elements read base[0] and discard it).
+template <typename OK, typename IDX>
+__device__ __forceinline__ void fetch_tile64(const double* __restrict__ base, OK ok, IDX idx,
+                                             double (&v)[16]) {
 #pragma unroll
-  for (int r = 0; r < 4; ++r)
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const int i = 4 * ty + r, j = 4 * tx + c;
-      double v = (i == j) ? 1.0 : 0.0;              // identity padding of a ragged last block
-      if (i < nb && j < nb)
-        v = (j >= i) ? A[(long)(p0 + i) * d + p0 + j] : A[(long)(p0 + j) * d + p0 + i];
-      a[r][c] = v;
-    }
-  // panel tile (coalesced), used after the factorisation
-  const int r0 = blockIdx.x * NB;
-  if (n_above > 0) {
-    for (int e = tid; e < NB * NB; e += 256) {
-      const int i = e / NB, j = e % NB;
-      sA[i][j] = (r0 + i < p0 && j < nb) ? A[(long)(r0 + i) * d + p0 + j] : 0.0;
-    }
+  for (int t = 0; t < 16; ++t) {
+    const int e = threadIdx.x + 256 * t;
+    const int i = e >> 6, j = e & 63;
+    const bool in = ok(i, j);
+    const double x = base[in ? idx(i, j) : 0L];
+    v[t] = in ? x : 0.0;
   }
+}
+template <typename ROW>
+__device__ __forceinline__ void put_tile64(ROW* s, const double (&v)[16]) {
+#pragma unroll
+  for (int t = 0; t < 16; ++t) {
+    const int e = threadIdx.x + 256 * t;
+    s[e >> 6][e & 63] = v[t];
+  }
+}
 
+// Reversed Cholesky of one 64 x 64 block held in registers: D = R R^T, R upper, columns taken
+// from the last to the first.  Thread (ty, tx) of 256 keeps the 4 x 4 sub-block rows 4ty..,
+// cols 4tx.. in `a` (the full symmetric block).  Per column: one LDS broadcast of the current
+// column, one barrier, one reciprocal and a rank-1 update  a -= col col^T / pivot.  On return
+// (after a barrier) sR holds R (zero below the diagonal) and sInvD[j] = 1 / R_jj; the square
+// roots are taken once, off the critical path.  A non-positive pivot is reported as column
+// p0 + j + 1 (by the work-group with `report`) and replaced by 1.
+__device__ __forceinline__ void factor64(double (&a)[4][4], double (*sR)[NB + 1],
+                                         double (*col)[NB], double* sInvD, int* info, int p0,
+                                         bool report) {
+  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
 #pragma unroll 1
   for (int jb = NB / 4 - 1; jb >= 0; --jb) {
 #pragma unroll
@@ -125,7 +124,7 @@ __global__ __launch_bounds__(256) void panel_factor_kernel(double* __restrict__ 
       __syncthreads();
       double piv = cbuf[j];
       if (!(piv > 0.0)) {
-        if (tid == 0 && blockIdx.x == 0) atomicCAS(info, 0, p0 + j + 1);
+        if (tid == 0 && report) atomicCAS(info, 0, p0 + j + 1);
         piv = 1.0;
       }
       const double ip = fast_rcp(piv);
@@ -145,36 +144,85 @@ __global__ __launch_bounds__(256) void panel_factor_kernel(double* __restrict__ 
     }
   }
   __syncthreads();
-  // R[:, j] = column_j / sqrt(pivot_j): the square roots are taken once, off the critical path
   if (tid < NB) sInvD[tid] = 1.0 / sqrt(sInvD[tid]);
   __syncthreads();
   for (int e = tid; e < NB * NB; e += 256) {
     const int i = e / NB, j = e % NB;
-    sR[i][j] *= sInvD[j];
+    sR[i][j] *= sInvD[j];                              // R[:, j] = column_j / sqrt(pivot_j)
   }
   __syncthreads();
+}
+
+// Row `row` of the tile sX: x R^T = a by substitution from the last column: x_j = rem_j / R_jj,
+// then rem_k -= x_j R[k][j] for every k < j (independent updates: no serial dot product).
+__device__ __forceinline__ void trsm_row(double (*sX)[NB + 1], int row, const double (*sR)[NB + 1],
+                                         const double* sInvD) {
+  double x[NB];
+#pragma unroll
+  for (int j = 0; j < NB; ++j) x[j] = sX[row][j];
+#pragma unroll
+  for (int j = NB - 1; j >= 0; --j) {
+    x[j] *= sInvD[j];
+#pragma unroll
+    for (int k = 0; k < j; ++k) x[k] = fma(-x[j], sR[k][j], x[k]);
+  }
+#pragma unroll
+  for (int j = 0; j < NB; ++j) sX[row][j] = x[j];
+}
+
+// The symmetric 64 x 64 block at (p0, p0) into the register tiling of factor64 (only the upper
+// triangle of A is valid); identity padding beyond nb.
+__device__ __forceinline__ void load_diag_block(const double* __restrict__ A, int d, int p0, int nb,
+                                                double (&a)[4][4]) {
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int i = 4 * ty + r, j = 4 * tx + c;
+      const bool in = i < nb && j < nb;
+      const int lo = i < j ? i : j, hi = i < j ? j : i;
+      const double x = A[in ? (long)(p0 + lo) * d + p0 + hi : 0L];
+      a[r][c] = in ? x : ((i == j) ? 1.0 : 0.0);
+    }
+}
+
+// Panel step of the reversed Cholesky for ONE 64-column panel, one work-group (256 threads) per
+// 64 rows of the panel.
+//   (1) every work-group factors the 64 x 64 diagonal block for itself (factor64);
+//   (2) rows [64 b, 64 b + 64) of the panel above the block: X R^T = A12, one thread per row.
+// Work-group 0 also writes R of the diagonal block to Rdiag (NB x NB, row-major, zero below the
+// diagonal, identity-padded), clears the block's pair flag and reports a non-positive pivot.
+// Launch with max(p, 1) work-groups, p = number of 64-row blocks above the diagonal block.
+__global__ __launch_bounds__(256) void panel_factor_kernel(double* __restrict__ A, int d, int p0,
+                                                           int nb, int n_above,
+                                                           double* __restrict__ Rdiag,
+                                                           int* __restrict__ pair_flag, int* info) {
+  __shared__ double sR[NB][NB + 1];     // R (upper) of the diagonal block
+  __shared__ double sA[NB][NB + 1];     // panel tile of this work-group
+  __shared__ double col[2][NB];
+  __shared__ double sInvD[NB];
+  const int tid = threadIdx.x;
+
+  double a[4][4];
+  load_diag_block(A, d, p0, nb, a);
+  // panel tile (coalesced), used after the factorisation
+  const int r0 = blockIdx.x * NB;
+  if (n_above > 0) {
+    double v[16];
+    fetch_tile64(A, [&](int i, int j) { return r0 + i < p0 && j < nb; },
+                 [&](int i, int j) { return (long)(r0 + i) * d + p0 + j; }, v);
+    put_tile64(sA, v);
+  }
+  factor64(a, sR, col, sInvD, info, p0, blockIdx.x == 0);
   // R of the diagonal block goes to its own buffer: the block itself must stay untouched, because
   // work-groups of this launch that start later still have to read it
   if (blockIdx.x == 0) {
     for (int e = tid; e < NB * NB; e += 256) Rdiag[e] = sR[e / NB][e % NB];
+    if (tid == 0) *pair_flag = 0;
   }
   if (n_above == 0) return;
-
-  // (2) X R^T = A12 by substitution from the last column: x_j = rem_j / R_jj, then
-  //     rem_k -= x_j R[k][j] for every k < j (independent updates: no serial dot product)
-  if (tid < NB) {
-    double x[NB];
-#pragma unroll
-    for (int j = 0; j < NB; ++j) x[j] = sA[tid][j];
-#pragma unroll
-    for (int j = NB - 1; j >= 0; --j) {
-      x[j] *= sInvD[j];
-#pragma unroll
-      for (int k = 0; k < j; ++k) x[k] = fma(-x[j], sR[k][j], x[k]);
-    }
-#pragma unroll
-    for (int j = 0; j < NB; ++j) sA[tid][j] = x[j];
-  }
+  if (tid < NB) trsm_row(sA, tid, sR, sInvD);
   __syncthreads();
   for (int e = tid; e < NB * NB; e += 256) {
     const int i = e / NB, j = e % NB;
@@ -184,8 +232,11 @@ __global__ __launch_bounds__(256) void panel_factor_kernel(double* __restrict__ 
 
 // Inverses of all diagonal blocks of R at once (one work-group per block, thread c solves
 // R x = e_c by back substitution); the inverse replaces the diagonal block of A (upper part,
-// zeros below), which until now still held the unfactored block.
+// zeros below), which until now still held the unfactored block.  A block that was the second of
+// a panel pair also brings its R12 (rows of the block before it) from the side buffer into A.
 __global__ __launch_bounds__(64) void diag_inverse_kernel(const double* __restrict__ Rdiag,
+                                                          const double* __restrict__ R12buf,
+                                                          const int* __restrict__ pair_flag,
                                                           double* __restrict__ A, int d) {
   __shared__ double s[NB][NB + 1];
   __shared__ double x[NB][NB + 1];
@@ -208,6 +259,13 @@ __global__ __launch_bounds__(64) void diag_inverse_kernel(const double* __restri
   for (int e = c; e < NB * NB; e += 64) {
     const int i = e / NB, j = e % NB;
     if (i < nb && j < nb) A[(long)(p0 + i) * d + p0 + j] = (j >= i) ? x[i][j] : 0.0;
+  }
+  if (pair_flag[blockIdx.x]) {
+    const double* r12 = R12buf + (long)blockIdx.x * NB * NB;
+    for (int e = c; e < NB * NB; e += 64) {
+      const int i = e / NB, j = e % NB;
+      if (j < nb) A[(long)(p0 - NB + i) * d + p0 + j] = r12[e];
+    }
   }
 }
 
@@ -266,6 +324,101 @@ __device__ __forceinline__ void quad_for_each(const Quad64& q, F f) {
           q.c[i][j][r]);
 }
 
+// Two adjacent 64-column panels -- block b1 (columns p1 ..) and block b2 = b1 + 1 -- in one
+// launch, one work-group per 64 rows above them.  With the diagonal 128 x 128 block
+// [D11 D12; D12^T D22] every work-group computes for itself
+//     D22 = R22 R22^T,   R12 = D12 R22^-T,   D11 - R12 R12^T = R11 R11^T
+// and for its own rows [A1 A2] of the two panels
+//     X2 = A2 R22^-T,    X1 = (A1 - X2 R12^T) R11^-T.
+// The two small products run on the fp64 matrix cores.  This halves the number of dependent
+// launches of the panel chain (each is short and latency-bound).  Work-group 0 writes R11, R22
+// to Rdiag and R12 to R12buf (never into A, whose blocks later-scheduled work-groups still
+// read) and sets the pair flag of b2, so that the inverse step puts R12 in place.
+constexpr size_t kPairLdsBytes = (size_t)(4 * NB * (NB + 1) + 3 * NB) * sizeof(double);
+
+__global__ __launch_bounds__(256) void panel_pair_kernel(double* __restrict__ A, int d, int p1,
+                                                         int nb2, int n_above,
+                                                         double* __restrict__ Rdiag1,
+                                                         double* __restrict__ Rdiag2,
+                                                         double* __restrict__ R12buf,
+                                                         int* __restrict__ pair_flag1,
+                                                         int* __restrict__ pair_flag2, int* info) {
+  extern __shared__ double dyn[];
+  typedef double Row[NB + 1];
+  Row* sR = reinterpret_cast<Row*>(dyn);            // R22, then R12 R12^T, then R11
+  Row* sR12 = sR + NB;                              // D12 -> R12
+  Row* sA1 = sR12 + NB;                             // own rows, columns of b1
+  Row* sA2 = sA1 + NB;                              // own rows, columns of b2
+  double (*col)[NB] = reinterpret_cast<double (*)[NB]>(dyn + 4 * NB * (NB + 1));
+  double* sInvD = dyn + 4 * NB * (NB + 1) + 2 * NB;
+  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+  const int p2 = p1 + NB;
+  const int r0 = blockIdx.x * NB;
+  const bool first = blockIdx.x == 0;
+
+  double a[4][4], a1[4][4];
+  load_diag_block(A, d, p2, nb2, a);                // D22
+  load_diag_block(A, d, p1, NB, a1);                // D11, needed after the first factorisation
+  {
+    double v12[16], v1[16], v2[16];
+    fetch_tile64(A, [&](int, int j) { return j < nb2; },
+                 [&](int i, int j) { return (long)(p1 + i) * d + p2 + j; }, v12);
+    if (n_above > 0) {
+      fetch_tile64(A, [&](int i, int) { return r0 + i < p1; },
+                   [&](int i, int j) { return (long)(r0 + i) * d + p1 + j; }, v1);
+      fetch_tile64(A, [&](int i, int j) { return r0 + i < p1 && j < nb2; },
+                   [&](int i, int j) { return (long)(r0 + i) * d + p2 + j; }, v2);
+      put_tile64(sA1, v1);
+      put_tile64(sA2, v2);
+    }
+    put_tile64(sR12, v12);
+  }
+  factor64(a, sR, col, sInvD, info, p2, first);
+  if (first)
+    for (int e = tid; e < NB * NB; e += 256) Rdiag2[e] = sR[e / NB][e % NB];
+  // R12 = D12 R22^-T (wavefront 0) and X2 = A2 R22^-T (wavefront 1), one thread per row
+  if (tid < NB) trsm_row(sR12, tid, sR, sInvD);
+  else if (tid < 2 * NB && n_above > 0) trsm_row(sA2, tid - NB, sR, sInvD);
+  __syncthreads();
+  {
+    Quad64 q;
+    quad_zero(q);
+    quad_mfma_64<true>(sR12, sR12, q);              // R12 R12^T
+    quad_for_each(q, [&](int r, int c, double v) { sR[r][c] = v; });
+    if (n_above > 0) {
+      quad_zero(q);
+      quad_mfma_64<true>(sA2, sR12, q);             // X2 R12^T
+      quad_for_each(q, [&](int r, int c, double v) { sA1[r][c] -= v; });
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+#pragma unroll
+    for (int c = 0; c < 4; ++c) a1[r][c] -= sR[4 * ty + r][4 * tx + c];
+  factor64(a1, sR, col, sInvD, info, p1, first);    // its first barrier precedes any write to sR
+  if (first) {
+    for (int e = tid; e < NB * NB; e += 256) {
+      Rdiag1[e] = sR[e / NB][e % NB];
+      R12buf[e] = sR12[e / NB][e % NB];
+    }
+    if (tid == 0) {
+      *pair_flag1 = 0;
+      *pair_flag2 = 1;
+    }
+  }
+  if (n_above == 0) return;
+  if (tid < NB) trsm_row(sA1, tid, sR, sInvD);
+  __syncthreads();
+  for (int e = tid; e < NB * NB; e += 256) {
+    const int i = e / NB, j = e % NB;
+    if (r0 + i < p1) {
+      A[(long)(r0 + i) * d + p1 + j] = sA1[i][j];
+      if (j < nb2) A[(long)(r0 + i) * d + p2 + j] = sA2[i][j];
+    }
+  }
+}
+
 // Trailing update with the panel columns [k0, k0 + Kd):  A[i][j] -= sum_k A[i][k] A[j][k]  on the
 // upper 64 x 64 tiles (bi <= bj) whose block column bj lies in [cb0, cb1).  Used twice:
 //   inner: after each 64-column panel, only for the block columns of the same outer panel that
@@ -286,20 +439,34 @@ __global__ __launch_bounds__(256) void syrk_trailing_kernel(double* __restrict__
   const int k_end = (k0 + Kd < d) ? k0 + Kd : d;
   Quad64 q;
   quad_zero(q);
+  double vi[16], vj[16];
+  auto fetch = [&](int kc) {
+    fetch_tile64(A, [&](int, int k) { return kc + k < k_end; },
+                 [&](int i, int k) { return (long)(bi * NB + i) * d + kc + k; }, vi);
+    fetch_tile64(A, [&](int, int k) { return kc + k < k_end; },
+                 [&](int i, int k) { return (long)(bj * NB + i) * d + kc + k; }, vj);
+  };
+  fetch(k0);
   for (int kc = k0; kc < k_end; kc += NB) {
-    for (int e = tid; e < NB * NB; e += 256) {
-      const int i = e / NB, k = e % NB;
-      const bool in = kc + k < k_end;
-      si[i][k] = in ? A[(long)(bi * NB + i) * d + kc + k] : 0.0;
-      sj[i][k] = in ? A[(long)(bj * NB + i) * d + kc + k] : 0.0;
-    }
+    put_tile64(si, vi);
+    put_tile64(sj, vj);
     __syncthreads();
+    if (kc + NB < k_end) fetch(kc + NB);          // in flight during the products below
     quad_mfma_64<true>(si, sj, q);
     __syncthreads();
   }
+  // read-modify-write of the 16 results of this lane, all loads first
+  double old[16];
+  int n = 0;
+  quad_for_each(q, [&](int r, int c, double) {
+    const int i = bi * NB + r, j = bj * NB + c;
+    old[n++] = A[(j >= i) ? (long)i * d + j : 0L];
+  });
+  n = 0;
   quad_for_each(q, [&](int r, int c, double v) {
     const int i = bi * NB + r, j = bj * NB + c;
-    if (j >= i) A[(long)i * d + j] -= v;
+    if (j >= i) A[(long)i * d + j] = old[n] - v;
+    ++n;
   });
 }
 
@@ -340,27 +507,36 @@ __global__ __launch_bounds__(256) void tri_inverse_level_kernel(double* __restri
   quad_zero(q);
   const int kb_begin = (MODE == 1) ? 0 : ti;
   const int kb_end = (MODE == 1) ? tj + 1 : Mb;
-  for (int kb = kb_begin; kb < kb_end; ++kb) {
-    for (int e = tid; e < NB * NB; e += 256) {
-      const int i = e / NB, j = e % NB;
-      double va, vb;
-      if (MODE == 1) {
-        // A operand: R12[row0+i][mid*NB + kb*NB + j];  B operand: U22[(mid+kb)*NB+i][col0+j]
-        const int gr = row0 + i, gc = (mid + kb) * NB + j;
-        va = (gr < d && gc < d) ? A[(long)gr * d + gc] : 0.0;
-        const int br = (mid + kb) * NB + i, bc = col0 + j;
-        vb = (br < d && bc < d && br <= bc) ? A[(long)br * d + bc] : 0.0;
-      } else {
-        // A operand: U11[row0+i][(lo+kb)*NB + j];  B operand: tmp[(lo+kb)*NB+i][tj*NB+j]
-        const int gr = row0 + i, gc = (lo + kb) * NB + j;
-        va = (gr < d && gc < d && gr <= gc) ? A[(long)gr * d + gc] : 0.0;
-        const int br = (lo + kb) * NB + i;
-        vb = (br < d) ? tmp[(long)br * ldt + tj * NB + j] : 0.0;
-      }
-      sa[i][j] = va;
-      sb[i][j] = vb;
+  double va[16], vb[16];
+  auto fetch = [&](int kb) {
+    if (MODE == 1) {
+      // A operand: R12[row0+i][(mid+kb)*NB + j];  B operand: U22[(mid+kb)*NB+i][col0+j]
+      fetch_tile64(A, [&](int i, int j) { return row0 + i < d && (mid + kb) * NB + j < d; },
+                   [&](int i, int j) { return (long)(row0 + i) * d + (mid + kb) * NB + j; }, va);
+      fetch_tile64(A,
+                   [&](int i, int j) {
+                     const int br = (mid + kb) * NB + i, bc = col0 + j;
+                     return br < d && bc < d && br <= bc;
+                   },
+                   [&](int i, int j) { return (long)((mid + kb) * NB + i) * d + col0 + j; }, vb);
+    } else {
+      // A operand: U11[row0+i][(lo+kb)*NB + j];  B operand: tmp[(lo+kb)*NB+i][tj*NB+j]
+      fetch_tile64(A,
+                   [&](int i, int j) {
+                     const int gr = row0 + i, gc = (lo + kb) * NB + j;
+                     return gr < d && gc < d && gr <= gc;
+                   },
+                   [&](int i, int j) { return (long)(row0 + i) * d + (lo + kb) * NB + j; }, va);
+      fetch_tile64(tmp, [&](int i, int) { return (lo + kb) * NB + i < d; },
+                   [&](int i, int j) { return (long)((lo + kb) * NB + i) * ldt + tj * NB + j; }, vb);
     }
+  };
+  if (kb_begin < kb_end) fetch(kb_begin);
+  for (int kb = kb_begin; kb < kb_end; ++kb) {
+    put_tile64(sa, va);
+    put_tile64(sb, vb);
     __syncthreads();
+    if (kb + 1 < kb_end) fetch(kb + 1);             // in flight during the products below
     quad_mfma_64<false>(sa, sb, q);
     __syncthreads();
   }
@@ -395,7 +571,7 @@ static int tree_depth(int P) {   // number of levels that contain at least one i
 }
 
 struct PrepLayout {
-  size_t a_off, tmp_off, rdiag_off, scal_off, total;
+  size_t a_off, tmp_off, rdiag_off, r12_off, flag_off, scal_off, total;
   int P, ldt;
 };
 
@@ -407,6 +583,8 @@ static PrepLayout prep_layout(int d) {
   L.a_off = off;    off += bpdq_align_up((size_t)d * d * sizeof(double), 256);
   L.tmp_off = off;  off += bpdq_align_up((size_t)d * L.ldt * sizeof(double), 256);
   L.rdiag_off = off; off += bpdq_align_up((size_t)L.P * NB * NB * sizeof(double), 256);
+  L.r12_off = off;  off += bpdq_align_up((size_t)L.P * NB * NB * sizeof(double), 256);
+  L.flag_off = off; off += bpdq_align_up((size_t)L.P * sizeof(int), 256);
   L.scal_off = off; off += 256;
   L.total = off;
   return L;
@@ -437,7 +615,16 @@ extern "C" int bpdq_prepare(const float* H, int d_in, float damp, float* U, unsi
   double* tmp = reinterpret_cast<double*>(base + L.tmp_off);
   double* Rdiag = reinterpret_cast<double*>(base + L.rdiag_off);
   double* scal = reinterpret_cast<double*>(base + L.scal_off);
+  double* R12buf = reinterpret_cast<double*>(base + L.r12_off);
+  int* pair_flag = reinterpret_cast<int*>(base + L.flag_off);
   const int d = d_in, P = L.P;
+  static bool attr_set = false;
+  if (!attr_set) {
+    BPDQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(panel_pair_kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)kPairLdsBytes));
+    attr_set = true;
+  }
 
   hipLaunchKernelGGL(prep_diag_kernel, dim3(1), dim3(1024), 0, stream, H, d, damp, dead, scal, info);
   BPDQ_LAUNCH_CHECK();
@@ -449,18 +636,34 @@ extern "C" int bpdq_prepare(const float* H, int d_in, float damp, float* U, unsi
   constexpr int kOuter = 8;
   for (int ob1 = P; ob1 > 0; ob1 -= kOuter) {
     const int ob0 = ob1 > kOuter ? ob1 - kOuter : 0;
-    for (int p = ob1 - 1; p >= ob0; --p) {
-      const int p0 = p * NB;
-      const int nb = (d - p0 < NB) ? d - p0 : NB;
-      hipLaunchKernelGGL(panel_factor_kernel, dim3(p > 0 ? p : 1), dim3(256), 0, stream, A, d, p0,
-                         nb, p, Rdiag + (size_t)p * NB * NB, info);
+    int p = ob1 - 1;
+    while (p >= ob0) {
+      int first_blk, width;                  // blocks [first_blk, p] factored by this launch
+      if (p - 1 >= ob0) {                    // a pair of panels
+        const int b1 = p - 1, p1 = b1 * NB;
+        const int nb2 = (d - p * NB < NB) ? d - p * NB : NB;
+        hipLaunchKernelGGL(panel_pair_kernel, dim3(b1 > 0 ? b1 : 1), dim3(256), kPairLdsBytes, stream,
+                           A, d, p1, nb2, b1, Rdiag + (size_t)b1 * NB * NB,
+                           Rdiag + (size_t)p * NB * NB, R12buf + (size_t)p * NB * NB,
+                           pair_flag + b1, pair_flag + p, info);
+        first_blk = b1;
+        width = NB + nb2;
+      } else {                               // a single panel (odd count at the left edge)
+        const int p0 = p * NB;
+        const int nb = (d - p0 < NB) ? d - p0 : NB;
+        hipLaunchKernelGGL(panel_factor_kernel, dim3(p > 0 ? p : 1), dim3(256), 0, stream, A, d, p0,
+                           nb, p, Rdiag + (size_t)p * NB * NB, pair_flag + p, info);
+        first_blk = p;
+        width = nb;
+      }
       BPDQ_LAUNCH_CHECK();
-      if (p > ob0) {
-        const int tiles = (p * (p + 1) - ob0 * (ob0 + 1)) / 2;
-        hipLaunchKernelGGL(syrk_trailing_kernel, dim3(tiles), dim3(256), 0, stream, A, d, p0, nb,
-                           ob0, p);
+      if (first_blk > ob0) {
+        const int tiles = (first_blk * (first_blk + 1) - ob0 * (ob0 + 1)) / 2;
+        hipLaunchKernelGGL(syrk_trailing_kernel, dim3(tiles), dim3(256), 0, stream, A, d,
+                           first_blk * NB, width, ob0, first_blk);
         BPDQ_LAUNCH_CHECK();
       }
+      p = first_blk - 1;
     }
     if (ob0 > 0) {
       hipLaunchKernelGGL(syrk_trailing_kernel, dim3(ob0 * (ob0 + 1) / 2), dim3(256), 0, stream, A, d,
@@ -469,7 +672,7 @@ extern "C" int bpdq_prepare(const float* H, int d_in, float damp, float* U, unsi
     }
   }
 
-  hipLaunchKernelGGL(diag_inverse_kernel, dim3(P), dim3(64), 0, stream, Rdiag, A, d);
+  hipLaunchKernelGGL(diag_inverse_kernel, dim3(P), dim3(64), 0, stream, Rdiag, R12buf, pair_flag, A, d);
   BPDQ_LAUNCH_CHECK();
   const int depth = tree_depth(P);
   for (int dd = depth - 1; dd >= 0; --dd) {
