@@ -130,6 +130,31 @@ int bpdq_coefs_to_fp16(const float* coefs, long n, uint16_t* out, void* stream);
 int bpdq_dequant_fp16(const uint32_t* planes, const uint16_t* coefs_h, int d_out, int d_in,
                       int bits, int group, float* W_hat, void* stream);
 
+/* ---- channel ordering around the pass (Sec. 4.1) --------------------------------------------
+ * The pass quantizes the columns left to right; a caller that wants another order permutes W and
+ * H first and carries `perm` with the stored layer.
+ * bpdq_channel_order: perm[i] = original index of the channel at position i.
+ *   group_size = 1: channels in descending order of H_jj (GPTQ's desc_act, Sec. 4.1); equal
+ *     values keep their index order.
+ *   group_size = g (divides d_in): every block of g consecutive channels stays together and in
+ *     order, blocks sorted by the descending sum of their H_jj (fp64, index order) -- a
+ *     group-preserving stand-in for the reordering the paper's experiments take from another
+ *     paper, not that method.
+ *   H: d_in x d_in, only the diagonal is read.  perm: d_in ints.  ws: 8-byte aligned,
+ *   bpdq_channel_order_workspace_bytes(d_in) bytes.
+ * bpdq_gather_columns:   Wp[r][i] = W[r][perm[i]]            (Wp must not alias W)
+ * bpdq_scatter_columns:  W[r][perm[i]] = Wp[r][i]            (inverse; e.g. W_hat back in place)
+ * bpdq_gather_symmetric: Hp[i][j] = H[perm[i]][perm[j]]      (H full/symmetrized; no aliasing)
+ * perm must be a permutation of 0..d_in-1 (not checked). */
+size_t bpdq_channel_order_workspace_bytes(int d_in);
+int bpdq_channel_order(const float* H, int d_in, int group_size, int* perm, void* ws,
+                       size_t ws_bytes, void* stream);
+int bpdq_gather_columns(const float* W, int d_out, int d_in, const int* perm, float* Wp,
+                        void* stream);
+int bpdq_scatter_columns(const float* Wp, int d_out, int d_in, const int* perm, float* W,
+                         void* stream);
+int bpdq_gather_symmetric(const float* H, int d_in, const int* perm, float* Hp, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -49,7 +49,7 @@ __all__ = [
     "hessian_accumulate", "prepare", "init_codes", "design_matrix", "fit_coefficients",
     "level_table", "nearest_level", "bitplane_sweep", "reconstruct", "solve_right",
     "round_coefficients", "bpdq_group", "uniform_frozen_group", "quantize_layer", "pack_planes", "unpack_planes", "dequant",
-    "layer_objective", "bits_per_weight",
+    "layer_objective", "bits_per_weight", "channel_order",
 ]
 
 
@@ -380,6 +380,29 @@ def dequant(planes, coef, group):
     for i in range(1, bits + 1):
         What = What + np.repeat(np.asarray(coef[i], dtype=np.float64), group, axis=1) * ((code >> (i - 1)) & 1)
     return What
+
+
+# --------------------------------------------------------------------------- #
+# Channel ordering around the pass (Sec. 4.1)
+# --------------------------------------------------------------------------- #
+def channel_order(H, group_size=1):
+    """Order in which the input channels are quantized.  Sec. 4.1: GPTQ's `desc_act` sorts the
+    channels in descending order of the (approximate) Hessian values, i.e. of diag(H)
+    (group_size = 1; equal values keep their index order).  The paper's own experiments use a
+    group-preserving reordering that another paper defines; the stand-in offered here
+    (group_size = g) keeps every block of g consecutive channels together and in order, and sorts
+    the blocks by the descending sum of their diagonal entries (summed in fp64 in index order).
+    Returns perm with perm[i] = original index of the channel at position i."""
+    diag = np.asarray(np.diag(np.asarray(H)), dtype=np.float64)
+    d = diag.shape[0]
+    if d % group_size:
+        raise ValueError("group_size must divide d_in")
+    blocks = diag.reshape(d // group_size, group_size)
+    key = np.zeros(d // group_size)
+    for m in range(group_size):
+        key = key + blocks[:, m]
+    order = np.argsort(-key, kind="stable")
+    return (order[:, None] * group_size + np.arange(group_size)[None, :]).reshape(-1).astype(np.int32)
 
 
 def bits_per_weight(bits, group, coef_bits=16):

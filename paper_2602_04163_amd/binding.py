@@ -21,6 +21,8 @@ EXPORTS = [
     "bpdq_prepare_workspace_bytes", "bpdq_prepare",
     "bpdq_quantize_workspace_bytes", "bpdq_quantize_layer",
     "bpdq_pack_planes", "bpdq_dequant", "bpdq_coefs_to_fp16", "bpdq_dequant_fp16",
+    "bpdq_channel_order_workspace_bytes", "bpdq_channel_order", "bpdq_gather_columns",
+    "bpdq_scatter_columns", "bpdq_gather_symmetric",
 ]
 
 
@@ -67,6 +69,16 @@ def load():
     lib.bpdq_dequant_fp16.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp]
     lib.bpdq_coefs_to_fp16.restype = ci
     lib.bpdq_coefs_to_fp16.argtypes = [vp, ctypes.c_long, vp, vp]
+    lib.bpdq_channel_order_workspace_bytes.restype = sz
+    lib.bpdq_channel_order_workspace_bytes.argtypes = [ci]
+    lib.bpdq_channel_order.restype = ci
+    lib.bpdq_channel_order.argtypes = [vp, ci, ci, vp, vp, sz, vp]
+    lib.bpdq_gather_columns.restype = ci
+    lib.bpdq_gather_columns.argtypes = [vp, ci, ci, vp, vp, vp]
+    lib.bpdq_scatter_columns.restype = ci
+    lib.bpdq_scatter_columns.argtypes = [vp, ci, ci, vp, vp, vp]
+    lib.bpdq_gather_symmetric.restype = ci
+    lib.bpdq_gather_symmetric.argtypes = [vp, ci, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -225,3 +237,46 @@ def bpdq_dequant_fp16(planes, coefs_h, group):
     _check(lib.bpdq_dequant_fp16(_ptr(planes), _ptr(coefs_h), d_out, d_in, bits, group, _ptr(W_hat),
                                  _stream()), "bpdq_dequant_fp16")
     return W_hat
+
+
+def bpdq_channel_order(H, group_size=1):
+    """perm (int32, d_in): channels by descending H_jj, or blocks of group_size channels by
+    descending block sum."""
+    lib = load()
+    _dev(H, torch.float32, "H")
+    d_in = H.shape[0]
+    perm = torch.empty(d_in, dtype=torch.int32, device=H.device)
+    ws = _workspace(lib.bpdq_channel_order_workspace_bytes(d_in), H.device)
+    _check(lib.bpdq_channel_order(_ptr(H), d_in, group_size, _ptr(perm), _ptr(ws), ws.numel(),
+                                  _stream()), "bpdq_channel_order")
+    return perm
+
+
+def bpdq_gather_columns(W, perm):
+    lib = load()
+    _dev(W, torch.float32, "W")
+    _dev(perm, torch.int32, "perm")
+    out = torch.empty_like(W)
+    _check(lib.bpdq_gather_columns(_ptr(W), W.shape[0], W.shape[1], _ptr(perm), _ptr(out), _stream()),
+           "bpdq_gather_columns")
+    return out
+
+
+def bpdq_scatter_columns(Wp, perm):
+    lib = load()
+    _dev(Wp, torch.float32, "Wp")
+    _dev(perm, torch.int32, "perm")
+    out = torch.empty_like(Wp)
+    _check(lib.bpdq_scatter_columns(_ptr(Wp), Wp.shape[0], Wp.shape[1], _ptr(perm), _ptr(out),
+                                    _stream()), "bpdq_scatter_columns")
+    return out
+
+
+def bpdq_gather_symmetric(H, perm):
+    lib = load()
+    _dev(H, torch.float32, "H")
+    _dev(perm, torch.int32, "perm")
+    out = torch.empty_like(H)
+    _check(lib.bpdq_gather_symmetric(_ptr(H), H.shape[0], _ptr(perm), _ptr(out), _stream()),
+           "bpdq_gather_symmetric")
+    return out

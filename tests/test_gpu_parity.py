@@ -373,6 +373,71 @@ def test_whole_pass_tiny_config(dev):
     assert nd / (wl.bits * code.size) <= PLANE_TOL
 
 
+# ------------------------------------------------------------------ channel ordering
+@pytest.mark.parametrize("d_in,group_size", [(96, 1), (1000, 1), (384, 128), (2048, 64), (29568, 1)])
+def test_channel_order_matches_oracle(dev, d_in, group_size):
+    print(f"channel order d={d_in} gs={group_size}", flush=True)
+    rng = np.random.default_rng(d_in + group_size)
+    diag = (rng.random(d_in).astype(np.float32) * 10).round(1)      # rounded: plenty of ties
+    if d_in <= 2048:
+        H = torch.zeros(d_in, d_in)
+        H.diagonal().copy_(torch.from_numpy(diag))
+        Hd = H.to(dev)
+    else:                                   # only the diagonal is read: a strided view will do
+        Hd = torch.zeros(d_in * d_in, device=dev)
+        Hd[:: d_in + 1] = torch.from_numpy(diag).to(dev)
+        Hd = Hd.view(d_in, d_in)
+    perm = bq.bpdq_channel_order(Hd, group_size).cpu().numpy()
+    want = orc.channel_order(np.diag(diag.astype(np.float64)), group_size)
+    assert np.array_equal(perm, want)
+
+
+def test_gather_scatter_bit_exact_and_ordered_pass(dev):
+    """Columns in and out of the permuted order are exact copies; the pass run in descending
+    order of diag(H) gives a valid layer whose objective (under the original metric) equals its
+    own sum of scores, compared against the oracle run on the same permuted inputs."""
+    print("gather / scatter / ordered pass", flush=True)
+    d_out, d_in = 72, 256
+    wl, W, X = _problem("cfg3a_qwen7b_up", d_out, d_in, 4 * d_in)      # lognormal channel scales
+    Hd = torch.zeros(d_in, d_in, device=dev)
+    bq.bpdq_hessian_accumulate(X.to(dev), Hd, 2.0, True)
+    perm = bq.bpdq_channel_order(Hd)
+    pn = perm.cpu().numpy()
+    Hn = Hd.cpu().numpy()
+    assert np.array_equal(pn, orc.channel_order(Hn.astype(np.float64)))
+    Wp = bq.bpdq_gather_columns(W.to(dev), perm)
+    Hp = bq.bpdq_gather_symmetric(Hd, perm)
+    assert np.array_equal(Wp.cpu().numpy(), W.numpy()[:, pn])
+    assert np.array_equal(Hp.cpu().numpy(), Hn[np.ix_(pn, pn)])
+    assert torch.equal(bq.bpdq_scatter_columns(Wp, perm), W.to(dev))
+    U, dead, info = bq.bpdq_prepare(Hp, wl.damp)
+    assert int(info.item()) == 0
+    p = bq.make_params(3, 64, 128, 4, wl.alpha)
+    out = bq.bpdq_quantize_layer(Wp, U, dead, p)
+    What = bq.bpdq_scatter_columns(out["W_hat"], perm).cpu().numpy().astype(np.float64)
+    # oracle on the same permuted inputs and the same fp32 U
+    U64 = U.cpu().numpy().astype(np.float64)
+    ref = orc.quantize_layer(Wp.cpu().numpy(), U64, dead.cpu().numpy().astype(bool), 3, 64, 128, 4,
+                             alpha=float(np.float32(wl.alpha)))
+    code = orc.unpack_planes(out["planes"].cpu().numpy().view(np.uint32), d_in)
+    assert np.mean(code != ref["code"]) <= PLANE_TOL
+    Htp = np.linalg.inv(U64.T @ U64)                                  # damped metric, permuted order
+    inv = np.argsort(pn)
+    Ht = Htp[np.ix_(inv, inv)]                                        # ... back in the original order
+    Wn = W.numpy().astype(np.float64)
+    og = orc.layer_objective(Wn, What, Ht)
+    Wr = np.empty_like(ref["What"])
+    Wr[:, pn] = ref["What"]
+    orf = orc.layer_objective(Wn, Wr, Ht)
+    assert abs(og - orf) / orf <= OBJ_TOL
+    assert abs(float(out["grp_err"].sum().item()) - og) / og < 1e-3
+    # for reference: the natural order on the same layer
+    U0, dead0, _ = bq.bpdq_prepare(Hd, wl.damp)
+    out0 = bq.bpdq_quantize_layer(W.to(dev), U0, dead0, p)
+    o0 = orc.layer_objective(Wn, out0["W_hat"].cpu().numpy(), Ht)
+    print(f"   objective descending-diagonal order / natural order = {og / o0:.3f}", flush=True)
+
+
 # ------------------------------------------------------------------ storage helpers
 @pytest.mark.parametrize("bits", [1, 2, 3, 4])
 def test_pack_and_dequant_bit_exact(dev, bits):
