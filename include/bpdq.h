@@ -112,6 +112,21 @@ int bpdq_quantize_layer(const float* W, int d_out, int d_in, const float* U,
                         uint32_t* planes, float* coefs, float* W_hat, double* grp_err,
                         int* grp_iter, void* ws, size_t ws_bytes, void* stream);
 
+/* Layers that share one input (q/k/v, up/gate) share H and U; stacked by rows they go through the
+ * sweep in one call.  Every formula of the method is row-wise; only the choice of the kept
+ * iterate is made per weight matrix (Sec. 3.3), so it is made per layer here:
+ *   W       : the layers stacked by rows, d_out rows in all; planes / coefs / W_hat likewise.
+ *   seg_end : host array of n_seg (1..8) ascending row boundaries, seg_end[n_seg-1] == d_out;
+ *             every layer but the last must have a multiple of 16 rows.
+ *   grp_err, grp_iter : [n_seg][d_in/g].
+ * The results equal those of n_seg separate bpdq_quantize_layer calls bit for bit; the workspace
+ * is bpdq_quantize_workspace_bytes(d_out, d_in, p). */
+int bpdq_quantize_layers(const float* W, int d_out, int d_in, const float* U,
+                         const unsigned char* dead, const bpdq_params* p /* host */, int n_seg,
+                         const int* seg_end /* host */, uint32_t* planes, float* coefs,
+                         float* W_hat, double* grp_err, int* grp_iter, void* ws, size_t ws_bytes,
+                         void* stream);
+
 /* ---- storage format helpers (Eq. 1) -------------------------------------------------------
  * codes : uint8 d_out x d_in, bit (i-1) of a code is B_i.  planes as above. */
 int bpdq_pack_planes(const unsigned char* codes, int d_out, int d_in, int bits,

@@ -19,7 +19,7 @@ EXPORTS = [
     "bpdq_version",
     "bpdq_hessian_workspace_bytes", "bpdq_hessian_accumulate",
     "bpdq_prepare_workspace_bytes", "bpdq_prepare",
-    "bpdq_quantize_workspace_bytes", "bpdq_quantize_layer",
+    "bpdq_quantize_workspace_bytes", "bpdq_quantize_layer", "bpdq_quantize_layers",
     "bpdq_pack_planes", "bpdq_dequant", "bpdq_coefs_to_fp16", "bpdq_dequant_fp16",
     "bpdq_channel_order_workspace_bytes", "bpdq_channel_order", "bpdq_gather_columns",
     "bpdq_scatter_columns", "bpdq_gather_symmetric",
@@ -61,6 +61,9 @@ def load():
     lib.bpdq_quantize_workspace_bytes.argtypes = [ci, ci, pp]
     lib.bpdq_quantize_layer.restype = ci
     lib.bpdq_quantize_layer.argtypes = [vp, ci, ci, vp, vp, pp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.bpdq_quantize_layers.restype = ci
+    lib.bpdq_quantize_layers.argtypes = [vp, ci, ci, vp, vp, pp, ci, ctypes.POINTER(ci), vp, vp, vp,
+                                         vp, vp, vp, sz, vp]
     lib.bpdq_pack_planes.restype = ci
     lib.bpdq_pack_planes.argtypes = [vp, ci, ci, ci, vp, vp]
     lib.bpdq_dequant.restype = ci
@@ -192,6 +195,37 @@ def bpdq_quantize_layer(W, U, dead, params: BpdqParams, want_w_hat=True, ws=None
                                  _ptr(out["grp_err"]), _ptr(out["grp_iter"]), _ptr(ws), ws.numel(),
                                  _stream())
     _check(rc, "bpdq_quantize_layer")
+    return out
+
+
+def bpdq_quantize_layers(W, seg_end, U, dead, params: BpdqParams, want_w_hat=True, ws=None):
+    """Layers sharing one U, stacked by rows (seg_end = ascending row boundaries).  Returns the
+    same dict as bpdq_quantize_layer with grp_err / grp_iter of shape (n_seg, d_in/g)."""
+    lib = load()
+    _dev(W, torch.float32, "W")
+    _dev(U, torch.float32, "U")
+    d_out, d_in = W.shape
+    k, g = params.bits, params.group
+    dev = W.device
+    n_seg = len(seg_end)
+    out = dict(
+        planes=torch.empty((k, d_out, d_in // 32), dtype=torch.int32, device=dev),
+        coefs=torch.empty((k + 1, d_out, d_in // g), dtype=torch.float32, device=dev),
+        W_hat=torch.empty((d_out, d_in), dtype=torch.float32, device=dev) if want_w_hat else None,
+        grp_err=torch.empty((n_seg, d_in // g), dtype=torch.float64, device=dev),
+        grp_iter=torch.empty((n_seg, d_in // g), dtype=torch.int32, device=dev),
+    )
+    if ws is None:
+        need = lib.bpdq_quantize_workspace_bytes(d_out, d_in, ctypes.byref(params))
+        if need == 0:
+            raise BpdqError("bpdq_quantize_workspace_bytes: invalid parameters")
+        ws = _workspace(need, dev)
+    seg = (ctypes.c_int * n_seg)(*[int(e) for e in seg_end])
+    rc = lib.bpdq_quantize_layers(_ptr(W), d_out, d_in, _ptr(U), _ptr(dead), ctypes.byref(params),
+                                  n_seg, seg, _ptr(out["planes"]), _ptr(out["coefs"]),
+                                  _ptr(out["W_hat"]), _ptr(out["grp_err"]), _ptr(out["grp_iter"]),
+                                  _ptr(ws), ws.numel(), _stream())
+    _check(rc, "bpdq_quantize_layers")
     return out
 
 

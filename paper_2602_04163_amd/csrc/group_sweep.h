@@ -394,6 +394,14 @@ struct TailArgs {
   int first_wg;      // work-groups below this index sweep
 };
 
+// Layers that share one input share U and go through the sweep stacked by rows; the best
+// iterate of a group is chosen per layer (segment).  Boundaries in work-groups of 16 rows.
+constexpr int kMaxSegments = 8;
+struct SegArgs {
+  int n_seg;
+  int wg_end[kMaxSegments];   // ascending; wg_end[n_seg - 1] = number of sweeping work-groups
+};
+
 // W'[:, c_begin:c_end] -= Et^T U[k0:k0+Kd, c_begin:c_end], one 128 x 128 tile per work-group
 __device__ __forceinline__ void tail_role(const TailArgs& ta, const float* __restrict__ U, int ldu,
                                           int lde, int ldw, int d_out) {
@@ -665,27 +673,38 @@ __global__ __launch_bounds__(kSweepThreads, kSweepWavesPerSimd<G>) void uniform_
 }
 
 // Selection + commit of one group, 16 rows per work-group (same lane mapping as the sweep).
-// Every work-group first sums the row-block scores of each iterate in one fixed order and takes
-// the earliest minimum (Sec. 3.3: keep the iterate with the smallest ||E_group||_F^2), so all
-// work-groups agree bit for bit; work-group 0 publishes grp_iter / grp_err.  Then the kept
+// Every work-group first sums the row-block scores of each iterate over its own layer (segment)
+// in one fixed order and takes the earliest minimum (Sec. 3.3: keep the iterate with the smallest
+// ||E_group||_F^2), so all work-groups of a layer agree bit for bit; the first work-group of a
+// segment publishes grp_iter / grp_err (arrays of n_grp entries per segment).  Then the kept
 // iterate is written out: packed planes (wave ballots), coefficients, What, and E* transposed
 // into the K-major error buffer Eblk[(s0 - b0) + j][row] (leading dimension lde).
 template <int K, int G>
 __global__ __launch_bounds__(256) void commit_group_kernel(
     const unsigned char* __restrict__ cand_codes, const float* __restrict__ cand_coef,
     const float* __restrict__ cand_E, const double* __restrict__ cand_score, int n_wg, int T,
-    double* __restrict__ grp_err, int* __restrict__ grp_iter, int d_out, int d_in, int s0, int b0,
+    SegArgs seg, double* __restrict__ grp_err, int* __restrict__ grp_iter, int d_out, int d_in,
+    int s0, int b0,
     uint32_t* __restrict__ planes, float* __restrict__ coefs, float* __restrict__ W_hat,
     float* __restrict__ Eblk, int lde) {
   constexpr int CPL = G / 16;
   __shared__ double tot[64];
   __shared__ float sE[G][17];
   const int tid = threadIdx.x, lane16 = tid & 15;
+  // my segment (work-groups past the last row belong to the last one; they write nothing)
+  int wg_lo = 0, wg_hi = seg.wg_end[0], si = 0;
+#pragma unroll
+  for (int q = 1; q < kMaxSegments; ++q)
+    if (q < seg.n_seg && (int)blockIdx.x >= seg.wg_end[q - 1]) {
+      wg_lo = seg.wg_end[q - 1];
+      wg_hi = seg.wg_end[q];
+      si = q;
+    }
   // iterate q is summed by wavefront q % 4: strided partial sums per lane, then a fixed
   // xor butterfly over the 64 lanes
   for (int q = tid >> 6; q <= T; q += 4) {
     double s = 0.0;
-    for (int w = tid & 63; w < n_wg; w += 64) s += cand_score[(long)q * n_wg + w];
+    for (int w = wg_lo + (tid & 63); w < wg_hi; w += 64) s += cand_score[(long)q * n_wg + w];
 #pragma unroll
     for (int m = 32; m > 0; m >>= 1) s += __shfl_xor(s, m, 64);
     if ((tid & 63) == 0) tot[q] = s;
@@ -694,9 +713,9 @@ __global__ __launch_bounds__(256) void commit_group_kernel(
   int it = 0;
   for (int q = 1; q <= T; ++q)
     if (tot[q] < tot[it]) it = q;
-  if (blockIdx.x == 0 && tid == 0) {
-    *grp_iter = it;
-    *grp_err = tot[it];
+  if ((int)blockIdx.x == wg_lo && tid == 0) {
+    grp_iter[(long)si * (d_in / G)] = it;
+    grp_err[(long)si * (d_in / G)] = tot[it];
   }
 
   const int row0 = blockIdx.x * kRowsPerWG;
@@ -779,9 +798,9 @@ static inline QuantLayout quant_layout(int d_out, int d_in, const bpdq_params& p
 // the tail role `ta` for the previous block, see above), then selection + commit.
 template <int K, int G>
 static inline int launch_group(hipStream_t stream, const float* Wp, int d_out, int d_in, const float* U,
-                        int s0, int kp0, TailArgs ta, const bpdq_params& p, const QuantLayout& L,
-                        char* base, uint32_t* planes, float* coefs, float* W_hat, double* grp_err,
-                        int* grp_iter) {
+                        int s0, int kp0, TailArgs ta, const SegArgs& seg, const bpdq_params& p,
+                        const QuantLayout& L, char* base, uint32_t* planes, float* coefs,
+                        float* W_hat, double* grp_err, int* grp_iter) {
   unsigned char* c_codes = reinterpret_cast<unsigned char*>(base + L.codes_off);
   float* c_coef = reinterpret_cast<float*>(base + L.coef_off);
   float* c_E = reinterpret_cast<float*>(base + L.e_off);
@@ -814,15 +833,15 @@ static inline int launch_group(hipStream_t stream, const float* Wp, int d_out, i
   }
   BPDQ_LAUNCH_CHECK();
   hipLaunchKernelGGL((commit_group_kernel<K, G>), dim3(L.lde / kRowsPerWG), dim3(256), 0, stream,
-                     c_codes, c_coef, c_E, c_score, L.n_wg, T, grp_err + gi, grp_iter + gi, d_out,
+                     c_codes, c_coef, c_E, c_score, L.n_wg, T, seg, grp_err + gi, grp_iter + gi, d_out,
                      d_in, s0, 0, planes, coefs, W_hat, Eall, L.lde);
   BPDQ_LAUNCH_CHECK();
   return 0;
 }
 
 typedef int (*GroupLauncher)(hipStream_t, const float*, int, int, const float*, int, int, TailArgs,
-                             const bpdq_params&, const QuantLayout&, char*, uint32_t*, float*,
-                             float*, double*, int*);
+                             const SegArgs&, const bpdq_params&, const QuantLayout&, char*, uint32_t*,
+                             float*, float*, double*, int*);
 
 // The group kernels are large, fully unrolled kernels: one translation unit per plane count
 // instantiates group sizes 32 / 64 / 128, and one more per plane count group size 256, which

@@ -115,21 +115,10 @@ extern "C" size_t bpdq_quantize_workspace_bytes(int d_out, int d_in, const bpdq_
   return quant_layout(d_out, d_in, *p).total;
 }
 
-extern "C" int bpdq_quantize_layer(const float* W, int d_out, int d_in, const float* U,
-                                   const unsigned char* dead, const bpdq_params* p,
-                                   uint32_t* planes, float* coefs, float* W_hat, double* grp_err,
-                                   int* grp_iter, void* ws, size_t ws_bytes, void* stream_) {
-  hipStream_t stream = static_cast<hipStream_t>(stream_);
-  if (!W || (reinterpret_cast<uintptr_t>(W) & 15)) return -1;
-  if (d_out <= 0) return -2;
-  if (d_in <= 0 || d_in % 32) return -3;
-  if (!U || (reinterpret_cast<uintptr_t>(U) & 15)) return -4;
-  if (check_params(d_out, d_in, p)) return -6;
-  if (!planes) return -7;
-  if (!coefs) return -8;
-  if (!grp_err) return -10;
-  if (!grp_iter) return -11;
-  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255)) return -12;
+static int quantize_rows(const float* W, int d_out, int d_in, const float* U,
+                         const unsigned char* dead, const bpdq_params* p, const SegArgs& seg,
+                         uint32_t* planes, float* coefs, float* W_hat, double* grp_err,
+                         int* grp_iter, void* ws, size_t ws_bytes, hipStream_t stream) {
   const QuantLayout L = quant_layout(d_out, d_in, *p);
   if (ws_bytes < L.total) return -13;
   char* base = static_cast<char*>(ws);
@@ -162,12 +151,66 @@ extern "C" int bpdq_quantize_layer(const float* W, int d_out, int d_in, const fl
         ta.c_end = d_in;
         ta.tiles_n = bpdq_ceil_div(d_in - b1, TailGemm::kTileN);
       }
-      const int rc = group(stream, Wp, d_out, d_in, U, s0, kp0, ta, *p, L, base, planes, coefs,
+      const int rc = group(stream, Wp, d_out, d_in, U, s0, kp0, ta, seg, *p, L, base, planes, coefs,
                            W_hat, grp_err, grp_iter);
       if (rc) return rc;
     }
   }
   return 0;
+}
+
+extern "C" int bpdq_quantize_layer(const float* W, int d_out, int d_in, const float* U,
+                                   const unsigned char* dead, const bpdq_params* p,
+                                   uint32_t* planes, float* coefs, float* W_hat, double* grp_err,
+                                   int* grp_iter, void* ws, size_t ws_bytes, void* stream_) {
+  if (!W || (reinterpret_cast<uintptr_t>(W) & 15)) return -1;
+  if (d_out <= 0) return -2;
+  if (d_in <= 0 || d_in % 32) return -3;
+  if (!U || (reinterpret_cast<uintptr_t>(U) & 15)) return -4;
+  if (check_params(d_out, d_in, p)) return -6;
+  if (!planes) return -7;
+  if (!coefs) return -8;
+  if (!grp_err) return -10;
+  if (!grp_iter) return -11;
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255)) return -12;
+  SegArgs seg{};
+  seg.n_seg = 1;
+  seg.wg_end[0] = bpdq_ceil_div(d_out, kRowsPerWG);
+  return quantize_rows(W, d_out, d_in, U, dead, p, seg, planes, coefs, W_hat, grp_err, grp_iter, ws,
+                       ws_bytes, static_cast<hipStream_t>(stream_));
+}
+
+extern "C" int bpdq_quantize_layers(const float* W, int d_out, int d_in, const float* U,
+                                    const unsigned char* dead, const bpdq_params* p, int n_seg,
+                                    const int* seg_end, uint32_t* planes, float* coefs,
+                                    float* W_hat, double* grp_err, int* grp_iter, void* ws,
+                                    size_t ws_bytes, void* stream_) {
+  if (!W || (reinterpret_cast<uintptr_t>(W) & 15)) return -1;
+  if (d_out <= 0) return -2;
+  if (d_in <= 0 || d_in % 32) return -3;
+  if (!U || (reinterpret_cast<uintptr_t>(U) & 15)) return -4;
+  if (check_params(d_out, d_in, p)) return -6;
+  if (n_seg < 1 || n_seg > kMaxSegments) return -7;
+  if (!seg_end) return -8;
+  SegArgs seg{};
+  seg.n_seg = n_seg;
+  int prev = 0;
+  for (int s = 0; s < n_seg; ++s) {
+    const int e = seg_end[s];
+    // every layer but the last must end on a work-group boundary (16 rows)
+    if (e <= prev || e > d_out || (s + 1 < n_seg && e % kRowsPerWG)) return -8;
+    seg.wg_end[s] = bpdq_ceil_div(e, kRowsPerWG);
+    prev = e;
+  }
+  if (prev != d_out) return -8;
+  if (!planes) return -9;
+  if (!coefs) return -10;
+  if (!grp_err) return -12;
+  if (!grp_iter) return -13;
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255)) return -14;
+  const int rc = quantize_rows(W, d_out, d_in, U, dead, p, seg, planes, coefs, W_hat, grp_err,
+                               grp_iter, ws, ws_bytes, static_cast<hipStream_t>(stream_));
+  return rc == -13 ? -15 : rc;
 }
 
 extern "C" int bpdq_pack_planes(const unsigned char* codes, int d_out, int d_in, int bits,

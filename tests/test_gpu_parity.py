@@ -373,6 +373,39 @@ def test_whole_pass_tiny_config(dev):
     assert nd / (wl.bits * code.size) <= PLANE_TOL
 
 
+def test_stacked_layers_equal_separate_calls(dev):
+    """q/k/v-style layers that share one U, stacked by rows in one call: every output must equal
+    the separate calls bit for bit, the kept iterate being chosen per layer."""
+    print("stacked layers sharing U", flush=True)
+    d_in = 384
+    rows = [112, 48, 40]                     # the last one is ragged (not a multiple of 16)
+    wl, W, X = _problem("cfg2_qwen7b_attn", sum(rows), d_in, 4 * d_in)
+    W[rows[0]:rows[0] + rows[1]] *= 7.0      # different scales: different iterates win per layer
+    H = np.zeros((d_in, d_in))
+    orc.hessian_accumulate(X.numpy(), H)
+    Uref, dead, info = orc.prepare(H, wl.damp)
+    U = torch.from_numpy(Uref.astype(np.float32)).to(dev)
+    p = bq.make_params(2, 128, 128, 5, wl.alpha)
+    Wd = W.to(dev)
+    ends = np.cumsum(rows).tolist()
+    both = bq.bpdq_quantize_layers(Wd, ends, U, None, p)
+    r0 = 0
+    for s, r1 in enumerate(ends):
+        one = bq.bpdq_quantize_layer(Wd[r0:r1].contiguous(), U, None, p)
+        assert torch.equal(both["planes"][:, r0:r1], one["planes"])
+        assert torch.equal(both["coefs"][:, r0:r1], one["coefs"])
+        assert torch.equal(both["W_hat"][r0:r1], one["W_hat"])
+        assert torch.equal(both["grp_iter"][s], one["grp_iter"])
+        assert torch.equal(both["grp_err"][s], one["grp_err"])
+        r0 = r1
+    it = both["grp_iter"].cpu().numpy()
+    print(f"   kept iterates per layer: {it.tolist()}", flush=True)
+    # argument checks: boundaries must ascend, end at d_out, and be multiples of 16 inside
+    for bad in ([100, 200], [112, 150, 200], [112, 112, 200], [200, 112]):
+        with pytest.raises(bq.BpdqError):
+            bq.bpdq_quantize_layers(Wd, bad, U, None, p)
+
+
 # ------------------------------------------------------------------ channel ordering
 @pytest.mark.parametrize("d_in,group_size", [(96, 1), (1000, 1), (384, 128), (2048, 64), (29568, 1)])
 def test_channel_order_matches_oracle(dev, d_in, group_size):

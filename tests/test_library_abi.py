@@ -68,5 +68,10 @@ def test_argument_errors_are_reported_without_a_gpu(lib):
     assert lib.bpdq_pack_planes(None, 4, 64, 2, None, None) == -1
     assert lib.bpdq_dequant(None, None, 4, 64, 2, 32, None, None) == -1
     assert lib.bpdq_dequant_fp16(None, None, 4, 64, 2, 32, None, None) == -1
+    assert lib.bpdq_quantize_layers(None, 4, 64, None, None, None, 1, None, None, None, None, None,
+                                    None, None, 0, None) == -1
+    assert lib.bpdq_channel_order(None, 64, 1, None, None, 0, None) == -1
+    assert lib.bpdq_gather_symmetric(None, 64, None, None, None) == -1
+    assert binding.load().bpdq_channel_order_workspace_bytes(3584) >= 3584 * 8
     assert lib.bpdq_coefs_to_fp16(None, 4, None, None) == -1
     assert lib.bpdq_coefs_to_fp16(None, 0, None, None) == 0       # nothing to convert
