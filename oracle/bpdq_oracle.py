@@ -49,7 +49,7 @@ __all__ = [
     "hessian_accumulate", "prepare", "init_codes", "design_matrix", "fit_coefficients",
     "level_table", "nearest_level", "bitplane_sweep", "reconstruct", "solve_right",
     "round_coefficients", "bpdq_group", "uniform_frozen_group", "quantize_layer", "pack_planes", "unpack_planes", "dequant",
-    "layer_objective", "bits_per_weight", "channel_order",
+    "layer_objective", "bits_per_weight", "channel_order", "gemv",
 ]
 
 
@@ -403,6 +403,12 @@ def channel_order(H, group_size=1):
         key = key + blocks[:, m]
     order = np.argsort(-key, kind="stable")
     return (order[:, None] * group_size + np.arange(group_size)[None, :]).reshape(-1).astype(np.int32)
+
+
+def gemv(planes, coef, group, x):
+    """y = What x for one token, from the stored format (Eq. 1, then a matrix-vector product),
+    fp64: the serving-side use of a quantized layer (Sec. 5)."""
+    return dequant(planes, coef, group) @ np.asarray(x, dtype=np.float64)
 
 
 def bits_per_weight(bits, group, coef_bits=16):

@@ -22,7 +22,7 @@ EXPORTS = [
     "bpdq_quantize_workspace_bytes", "bpdq_quantize_layer", "bpdq_quantize_layers",
     "bpdq_pack_planes", "bpdq_dequant", "bpdq_coefs_to_fp16", "bpdq_dequant_fp16",
     "bpdq_channel_order_workspace_bytes", "bpdq_channel_order", "bpdq_gather_columns",
-    "bpdq_scatter_columns", "bpdq_gather_symmetric",
+    "bpdq_scatter_columns", "bpdq_gather_symmetric", "bpdq_gemv",
 ]
 
 
@@ -72,6 +72,8 @@ def load():
     lib.bpdq_dequant_fp16.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp]
     lib.bpdq_coefs_to_fp16.restype = ci
     lib.bpdq_coefs_to_fp16.argtypes = [vp, ctypes.c_long, vp, vp]
+    lib.bpdq_gemv.restype = ci
+    lib.bpdq_gemv.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp, vp]
     lib.bpdq_channel_order_workspace_bytes.restype = sz
     lib.bpdq_channel_order_workspace_bytes.argtypes = [ci]
     lib.bpdq_channel_order.restype = ci
@@ -314,3 +316,20 @@ def bpdq_gather_symmetric(H, perm):
     _check(lib.bpdq_gather_symmetric(_ptr(H), H.shape[0], _ptr(perm), _ptr(out), _stream()),
            "bpdq_gather_symmetric")
     return out
+
+
+def bpdq_gemv(planes, coefs_h, group, x, y=None):
+    """y = What x for one token from the stored format (planes int32, coefficients float16)."""
+    lib = load()
+    _dev(planes, torch.int32, "planes")
+    _dev(coefs_h, torch.float16, "coefs_h")
+    _dev(x, torch.float32, "x")
+    bits, d_out, nw = planes.shape
+    d_in = nw * 32
+    if x.numel() != d_in:
+        raise BpdqError("x: expected d_in values")
+    if y is None:
+        y = torch.empty(d_out, dtype=torch.float32, device=planes.device)
+    _check(lib.bpdq_gemv(_ptr(planes), _ptr(coefs_h), d_out, d_in, bits, group, _ptr(x), _ptr(y),
+                         _stream()), "bpdq_gemv")
+    return y

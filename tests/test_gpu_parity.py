@@ -406,6 +406,50 @@ def test_stacked_layers_equal_separate_calls(dev):
             bq.bpdq_quantize_layers(Wd, bad, U, None, p)
 
 
+# ------------------------------------------------------------------ serving side
+@pytest.mark.parametrize("bits,group,d_out,d_in", [
+    (2, 128, 200, 384), (3, 64, 37, 320), (4, 32, 64, 2080), (1, 256, 19, 512), (2, 128, 515, 3584),
+])
+def test_gemv_from_stored_format(dev, bits, group, d_out, d_in):
+    """y = What x from packed planes + half coefficients against the oracle's Eq. 1 + matvec."""
+    print(f"gemv k={bits} g={group} {d_out}x{d_in}", flush=True)
+    rng = np.random.default_rng(bits * 1000 + d_in)
+    code = rng.integers(0, 1 << bits, size=(d_out, d_in)).astype(np.uint8)
+    coef = (rng.standard_normal((bits + 1, d_out, d_in // group)) * 0.02).astype(np.float16)
+    x = rng.standard_normal(d_in).astype(np.float32)
+    planes_np = orc.pack_planes(code, bits)
+    planes = torch.from_numpy(planes_np.view(np.int32)).to(dev)
+    y = bq.bpdq_gemv(planes, torch.from_numpy(coef).to(dev), group, torch.from_numpy(x).to(dev))
+    want = orc.gemv(planes_np, coef, group, x)
+    # fp32 accumulation: bound relative to sum |C_0| |x| + sum_i |C_i| b_i |x|
+    A = np.repeat(np.abs(coef[0].astype(np.float64)), group, axis=1)
+    for i in range(1, bits + 1):
+        A = A + np.repeat(np.abs(coef[i].astype(np.float64)), group, axis=1) * ((code >> (i - 1)) & 1)
+    bound = 1e-5 * (A @ np.abs(x.astype(np.float64))) + 1e-12
+    err = np.abs(y.cpu().numpy().astype(np.float64) - want)
+    print(f"   max err / bound = {np.max(err / bound):.3f}", flush=True)
+    assert np.all(err <= bound)
+
+
+def test_gemv_of_a_quantized_layer(dev):
+    print("gemv of a quantized layer (fp16 storage) + timing", flush=True)
+    wl, W, X = _problem("cfg2_qwen7b_attn", 512, 3584, 4096)
+    H = torch.zeros(3584, 3584, device=dev)
+    bq.bpdq_hessian_accumulate(X.to(dev), H, 2.0, True)
+    U, dead, info = bq.bpdq_prepare(H, wl.damp)
+    p = bq.make_params(2, 128, 128, 2, wl.alpha, coef_fp16=True)
+    out = bq.bpdq_quantize_layer(W.to(dev), U, dead, p)
+    ch = bq.bpdq_coefs_to_fp16(out["coefs"])
+    x = X[7].contiguous().to(dev)
+    y = bq.bpdq_gemv(out["planes"], ch, 128, x)
+    want = out["W_hat"].double() @ x.double()
+    scale = (out["W_hat"].double().abs() @ x.double().abs())
+    assert bool(((y.double() - want).abs() <= 2e-5 * scale + 1e-9).all())
+    # rejected sizes
+    with pytest.raises(bq.BpdqError):
+        bq.bpdq_gemv(out["planes"], ch, 48, x)
+
+
 # ------------------------------------------------------------------ channel ordering
 @pytest.mark.parametrize("d_in,group_size", [(96, 1), (1000, 1), (384, 128), (2048, 64), (29568, 1)])
 def test_channel_order_matches_oracle(dev, d_in, group_size):

@@ -72,6 +72,7 @@ def test_argument_errors_are_reported_without_a_gpu(lib):
                                     None, None, 0, None) == -1
     assert lib.bpdq_channel_order(None, 64, 1, None, None, 0, None) == -1
     assert lib.bpdq_gather_symmetric(None, 64, None, None, None) == -1
+    assert lib.bpdq_gemv(None, None, 4, 64, 2, 32, None, None, None) == -1
     assert binding.load().bpdq_channel_order_workspace_bytes(3584) >= 3584 * 8
     assert lib.bpdq_coefs_to_fp16(None, 4, None, None) == -1
     assert lib.bpdq_coefs_to_fp16(None, 0, None, None) == 0       # nothing to convert

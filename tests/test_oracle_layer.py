@@ -154,3 +154,24 @@ def test_bits_per_weight_matches_table1(golden_dir):
         planes = orc.pack_planes(np.zeros((d_out, d_in), dtype=np.uint8), k)
         n_coef = (k + 1) * d_out * (d_in // g)
         assert abs((planes.nbytes * 8 + 16 * n_coef) / (d_out * d_in) - bpw) < 0.006
+
+
+def test_gemv_is_dequant_then_matvec():
+    # the serving-side product from the stored format equals Eq. 1's What times x, and the
+    # regrouped form  sum_G (C_0 S(G) + sum_i C_i sum_{c in G} b_i x_c)  written out by hand
+    rng = np.random.default_rng(9)
+    d_out, d_in, g, k = 5, 64, 32, 3
+    code = rng.integers(0, 8, size=(d_out, d_in)).astype(np.uint8)
+    coef = rng.standard_normal((k + 1, d_out, d_in // g))
+    x = rng.standard_normal(d_in)
+    planes = orc.pack_planes(code, k)
+    y = orc.gemv(planes, coef, g, x)
+    want = np.zeros(d_out)
+    for r in range(d_out):
+        for G in range(d_in // g):
+            xs = x[G * g:(G + 1) * g]
+            want[r] += coef[0, r, G] * xs.sum()
+            for i in range(1, k + 1):
+                b = (code[r, G * g:(G + 1) * g] >> (i - 1)) & 1
+                want[r] += coef[i, r, G] * np.dot(b, xs)
+    assert np.allclose(y, want, rtol=1e-12, atol=1e-12)
