@@ -3,7 +3,8 @@
 //   y_r = sum_G ( C_0[r,G] S(G) + sum_i C_i[r,G] sum_{c in G} B_i[r,c] x_c ),   S(G) = sum_{c in G} x_c.
 // A weight costs one masked add per plane and no multiply; a row reads bits/8 bytes per weight.
 //
-// One wavefront per row (rows strided over the grid); lane l takes the 32-column words l, l + 64, ...
+// One wavefront per pair of rows (pairs strided over the grid); lane l takes the 32-column words
+// l, l + 64, ...
 // x is staged once per work-group in LDS, transposed (xT[j][w] = x[32 w + j]) so that the lanes
 // of a wavefront, which hold consecutive words, read consecutive addresses for every bit j.
 #include "common.h"
@@ -11,9 +12,11 @@
 namespace bpdq {
 
 constexpr int kGemvMaxDin = 36864;
+constexpr int kGemvThreads = 1024;   // 16 wavefronts share one staged copy of x and hide each other's loads
+constexpr int kGemvWaves = kGemvThreads / 64;
 
 template <int K>
-__global__ __launch_bounds__(256) void gemv_planes_kernel(const uint32_t* __restrict__ planes,
+__global__ __launch_bounds__(kGemvThreads) void gemv_planes_kernel(const uint32_t* __restrict__ planes,
                                                           const _Float16* __restrict__ coefs,
                                                           int d_out, int d_in, int group,
                                                           const float* __restrict__ x,
@@ -23,9 +26,9 @@ __global__ __launch_bounds__(256) void gemv_planes_kernel(const uint32_t* __rest
   float* xT = lds;                    // [32][nw]
   float* gs = lds + 32 * nw;          // S(G)
   const int tid = threadIdx.x;
-  for (int e = tid; e < d_in; e += 256) xT[(e & 31) * nw + (e >> 5)] = x[e];
+  for (int e = tid; e < d_in; e += kGemvThreads) xT[(e & 31) * nw + (e >> 5)] = x[e];
   __syncthreads();
-  for (int G = tid; G < n_grp; G += 256) {
+  for (int G = tid; G < n_grp; G += kGemvThreads) {
     float s = 0.f;
     for (int wq = 0; wq < wpg; ++wq)
       for (int j = 0; j < 32; ++j) s += xT[j * nw + G * wpg + wq];
@@ -33,34 +36,51 @@ __global__ __launch_bounds__(256) void gemv_planes_kernel(const uint32_t* __rest
   }
   __syncthreads();
   const int lane = tid & 63, wave = tid >> 6;
-  for (int r = blockIdx.x * 4 + wave; r < d_out; r += gridDim.x * 4) {
-    float acc = 0.f;
+  // two rows per wavefront and pass: their plane words are requested together
+  for (int r0 = (blockIdx.x * kGemvWaves + wave) * 2; r0 < d_out; r0 += gridDim.x * kGemvWaves * 2) {
+    const bool two = r0 + 1 < d_out;
+    const int r1 = two ? r0 + 1 : r0;
+    float acc0 = 0.f, acc1 = 0.f;
     for (int w = lane; w < nw; w += 64) {
-      uint32_t wd[K];
+      uint32_t wa[K], wb[K];
 #pragma unroll
-      for (int i = 0; i < K; ++i) wd[i] = planes[((long)i * d_out + r) * nw + w];
-      float m[K];
+      for (int i = 0; i < K; ++i) {
+        wa[i] = planes[((long)i * d_out + r0) * nw + w];
+        wb[i] = planes[((long)i * d_out + r1) * nw + w];
+      }
+      float ma[K], mb[K];
 #pragma unroll
-      for (int i = 0; i < K; ++i) m[i] = 0.f;
+      for (int i = 0; i < K; ++i) ma[i] = mb[i] = 0.f;
 #pragma unroll
       for (int j = 0; j < 32; ++j) {
-        const float xv = xT[j * nw + w];
+        const int xv = __builtin_bit_cast(int, xT[j * nw + w]);
 #pragma unroll
         for (int i = 0; i < K; ++i) {
           // all-ones where the bit is set: the masked add needs no compare
-          const int mask = __builtin_amdgcn_sbfe(static_cast<int>(wd[i]), j, 1);
-          m[i] += __builtin_bit_cast(float, __builtin_bit_cast(int, xv) & mask);
+          ma[i] += __builtin_bit_cast(float, xv & __builtin_amdgcn_sbfe(static_cast<int>(wa[i]), j, 1));
+          mb[i] += __builtin_bit_cast(float, xv & __builtin_amdgcn_sbfe(static_cast<int>(wb[i]), j, 1));
         }
       }
       const int G = w / wpg;
 #pragma unroll
-      for (int i = 0; i < K; ++i)
-        acc = fmaf((float)coefs[((long)(i + 1) * d_out + r) * n_grp + G], m[i], acc);
+      for (int i = 0; i < K; ++i) {
+        acc0 = fmaf((float)coefs[((long)(i + 1) * d_out + r0) * n_grp + G], ma[i], acc0);
+        acc1 = fmaf((float)coefs[((long)(i + 1) * d_out + r1) * n_grp + G], mb[i], acc1);
+      }
     }
-    for (int G = lane; G < n_grp; G += 64) acc = fmaf((float)coefs[(long)r * n_grp + G], gs[G], acc);
+    for (int G = lane; G < n_grp; G += 64) {
+      acc0 = fmaf((float)coefs[(long)r0 * n_grp + G], gs[G], acc0);
+      acc1 = fmaf((float)coefs[(long)r1 * n_grp + G], gs[G], acc1);
+    }
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
-    if (lane == 0) y[r] = acc;
+    for (int o = 32; o > 0; o >>= 1) {
+      acc0 += __shfl_xor(acc0, o, 64);
+      acc1 += __shfl_xor(acc1, o, 64);
+    }
+    if (lane == 0) {
+      y[r0] = acc0;
+      if (two) y[r1] = acc1;
+    }
   }
 }
 
@@ -81,8 +101,8 @@ extern "C" int bpdq_gemv(const uint32_t* planes, const uint16_t* coefs_h, int d_
   if (!y) return -8;
   const size_t lds = (size_t)(d_in + d_in / group) * sizeof(float);
   const _Float16* ch = reinterpret_cast<const _Float16*>(coefs_h);
-  int grid = bpdq_ceil_div(d_out, 4);
-  if (grid > 1024) grid = 1024;
+  int grid = bpdq_ceil_div(d_out, kGemvWaves * 2);   // 2 rows per wavefront and pass
+  if (grid > 256) grid = 256;                        // one work-group per CU; each stages x once
   auto launch = [&](auto kern) -> int {
     static bool attr_set = false;
     if (!attr_set) {
@@ -91,7 +111,7 @@ extern "C" int bpdq_gemv(const uint32_t* planes, const uint16_t* coefs_h, int d_
                                        (int)((kGemvMaxDin + kGemvMaxDin / 32) * sizeof(float))));
       attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, stream, planes, ch, d_out, d_in, group, x, y);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kGemvThreads), lds, stream, planes, ch, d_out, d_in, group, x, y);
     BPDQ_LAUNCH_CHECK();
     return 0;
   };
