@@ -373,6 +373,71 @@ def test_whole_pass_tiny_config(dev):
     assert nd / (wl.bits * code.size) <= PLANE_TOL
 
 
+@pytest.mark.parametrize("bits,group,block,iters,d_out,d_in", [
+    (2, 32, 32, 3, 1, 32),          # one row, one group, one plane word
+    (2, 128, 4096, 2, 17, 256),     # lazy block wider than the layer: no block update at all
+    (3, 32, 32, 63, 16, 64),        # the largest iteration count the library accepts
+    (2, 64, 64, 2, 16, 64),         # exactly one work-group, one group
+])
+def test_quantize_layer_degenerate_shapes(dev, bits, group, block, iters, d_out, d_in):
+    print(f"degenerate k={bits} g={group} B={block} T={iters} {d_out}x{d_in}", flush=True)
+    wl, W, X = _problem("cfg1_tiny", d_out, d_in, 4 * d_in)
+    H = np.zeros((d_in, d_in))
+    orc.hessian_accumulate(X.numpy(), H)
+    Uref, dead, info = orc.prepare(H, wl.damp)
+    U32 = Uref.astype(np.float32)
+    Ht = np.linalg.inv(U32.astype(np.float64).T @ U32.astype(np.float64))
+    ref, out = _run_both(dev, wl, W, U32, dead, bits, group, block, iters)
+    planes = out["planes"].cpu().numpy().view(np.uint32)
+    code = orc.unpack_planes(planes, d_in)
+    # tiny layers: a single near-tie can exceed a fractional tolerance, so compare what is unique:
+    # the objective, and that the result is a valid, self-consistent layer
+    Wn = W.numpy().astype(np.float64)
+    og = orc.layer_objective(Wn, out["W_hat"].cpu().numpy(), Ht)
+    orf = orc.layer_objective(Wn, ref["What"], Ht)
+    assert abs(og - orf) / orf <= 5e-3
+    assert abs(float(out["grp_err"].sum().item()) - og) / og < 1e-3
+    assert torch.equal(bq.bpdq_dequant(out["planes"], out["coefs"], group), out["W_hat"])
+    assert int(code.max()) < (1 << bits)
+    it = out["grp_iter"].cpu().numpy()
+    assert np.all(it >= 0) and np.all(it <= iters)
+
+
+def test_constant_rows_and_zero_weights(dev):
+    """Degenerate inputs of the method: a row that is constant inside a group (flat: hi == lo, all
+    codes 0 at initialisation) and an all-zero layer must give finite results and What == W."""
+    print("constant rows / zero weights", flush=True)
+    d_out, d_in, g = 32, 128, 64
+    wl, W, X = _problem("cfg1_tiny", d_out, d_in, 4 * d_in)
+    W[3, :] = 0.125                              # constant row
+    W[5, :64] = -0.5                             # constant inside the first group only
+    W[7, :] = 0.0
+    H = np.zeros((d_in, d_in))
+    orc.hessian_accumulate(X.numpy(), H)
+    Uref, dead, info = orc.prepare(H, wl.damp)
+    U32 = Uref.astype(np.float32)
+    ref, out = _run_both(dev, wl, W, U32, dead, 2, g, 64, 3)
+    What = out["W_hat"].cpu().numpy()
+    assert np.all(np.isfinite(What)) and np.all(np.isfinite(out["coefs"].cpu().numpy()))
+    # the relative ridge of the fit (alpha tr(G)/(k+1) with only the bias column active) shrinks
+    # the constant by alpha/(k+1): 1 / (1 + 1e-4 / 3)
+    shrink = 1.0 / (1.0 + wl.alpha / 3.0)
+    assert np.allclose(What[3], 0.125 * shrink, rtol=1e-6) and np.allclose(What[7], 0.0, atol=1e-9)
+    assert np.allclose(What[5, :64], -0.5 * shrink, rtol=1e-6)
+    assert np.allclose(What[[3, 5, 7]], ref["What"][[3, 5, 7]], rtol=1e-5, atol=1e-9)
+    Ht = np.linalg.inv(U32.astype(np.float64).T @ U32.astype(np.float64))
+    Wn = W.numpy().astype(np.float64)
+    og = orc.layer_objective(Wn, What, Ht)
+    orf = orc.layer_objective(Wn, ref["What"], Ht)
+    assert abs(og - orf) / orf <= OBJ_TOL
+    # an all-zero layer
+    Z = torch.zeros(16, d_in)
+    p = bq.make_params(2, g, 64, 2, wl.alpha)
+    outz = bq.bpdq_quantize_layer(Z.to(dev), torch.from_numpy(U32).to(dev), None, p)
+    assert float(outz["W_hat"].abs().max().item()) == 0.0
+    assert float(outz["grp_err"].abs().max().item()) == 0.0
+
+
 def test_stacked_layers_equal_separate_calls(dev):
     """q/k/v-style layers that share one U, stacked by rows in one call: every output must equal
     the separate calls bit for bit, the kept iterate being chosen per layer."""
