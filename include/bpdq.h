@@ -148,10 +148,11 @@ int bpdq_dequant_fp16(const uint32_t* planes, const uint16_t* coefs_h, int d_out
 /* ---- serving side: y = What x for one token, straight from the stored format (Sec. 5) -------
  * Eq. 1 regrouped per (row, group G):
  *   y_r = sum_G ( C_0[r,G] S(G) + sum_i C_i[r,G] sum_{c in G} B_i[r,c] x_c ),  S(G) = sum_{c in G} x_c
- * so a weight costs one masked add per plane and no multiply; the planes are read once
- * (bits/8 bytes per weight) and the coefficients as halves.  fp32 accumulation in a fixed order.
+ * so a weight costs no multiply: the inner sums come from a table of the 16 partial sums of every
+ * 4 consecutive x values.  The planes are read once (bits/8 bytes per weight), the coefficients
+ * as halves; fp32 accumulation in a fixed order.
  *   planes : as above;  coefs_h : half [bits+1][d_out][d_in/g];  x : float d_in;  y : float d_out.
- * Requirements: d_in % 32 == 0, 32 | group | d_in, d_in <= 36864 (x is staged in LDS). */
+ * Requirements: d_in % 32 == 0, 32 | group | d_in, x 16-byte aligned. */
 int bpdq_gemv(const uint32_t* planes, const uint16_t* coefs_h, int d_out, int d_in, int bits,
               int group, const float* x, float* y, void* stream);
 

@@ -3,83 +3,94 @@
 //   y_r = sum_G ( C_0[r,G] S(G) + sum_i C_i[r,G] sum_{c in G} B_i[r,c] x_c ),   S(G) = sum_{c in G} x_c.
 // A weight costs one masked add per plane and no multiply; a row reads bits/8 bytes per weight.
 //
-// One wavefront per pair of rows (pairs strided over the grid); lane l takes the 32-column words
-// l, l + 64, ...
-// x is staged once per work-group in LDS, transposed (xT[j][w] = x[32 w + j]) so that the lanes
-// of a wavefront, which hold consecutive words, read consecutive addresses for every bit j.
+// A look-up table replaces the per-bit work: for every segment of 4 columns the 16 partial sums
+// of its x values, T[seg][nibble]; a plane word then costs 8 (extract, look up, add) triples
+// instead of 32 masked adds.  The table of a chunk of up to 8192 columns (136 KB of LDS with
+// its padding) is built once per work-group and chunk -- 15 adds per segment -- and used by all
+// its rows.  One wavefront owns a pair of rows for the whole call (16 wavefronts per work-group,
+// one work-group per CU); lane l takes the 32-column words l, l + 64, ... of the chunk.  The row
+// stride of the table is 17 floats so that lanes with different nibbles fall into different banks.
 #include "common.h"
 
 namespace bpdq {
 
-constexpr int kGemvMaxDin = 36864;
-constexpr int kGemvThreads = 1024;   // 16 wavefronts share one staged copy of x and hide each other's loads
+constexpr int kGemvThreads = 1024;
 constexpr int kGemvWaves = kGemvThreads / 64;
+constexpr int kGemvChunk = 8192;                  // columns per table
+constexpr int kLutStride = 17;
+constexpr size_t kGemvLdsBytes = (size_t)((kGemvChunk / 4) * kLutStride + kGemvChunk / 32) * sizeof(float);
 
 template <int K>
 __global__ __launch_bounds__(kGemvThreads) void gemv_planes_kernel(const uint32_t* __restrict__ planes,
-                                                          const _Float16* __restrict__ coefs,
-                                                          int d_out, int d_in, int group,
-                                                          const float* __restrict__ x,
-                                                          float* __restrict__ y) {
+                                                                   const _Float16* __restrict__ coefs,
+                                                                   int d_out, int d_in, int group,
+                                                                   const float* __restrict__ x,
+                                                                   float* __restrict__ y) {
   extern __shared__ float lds[];
+  float* T = lds;                                        // [segments of the chunk][17]
+  float* Sw = lds + (kGemvChunk / 4) * kLutStride;       // sum of x over each word of the chunk
   const int nw = d_in / 32, n_grp = d_in / group, wpg = group / 32;
-  float* xT = lds;                    // [32][nw]
-  float* gs = lds + 32 * nw;          // S(G)
-  const int tid = threadIdx.x;
-  for (int e = tid; e < d_in; e += kGemvThreads) xT[(e & 31) * nw + (e >> 5)] = x[e];
-  __syncthreads();
-  for (int G = tid; G < n_grp; G += kGemvThreads) {
-    float s = 0.f;
-    for (int wq = 0; wq < wpg; ++wq)
-      for (int j = 0; j < 32; ++j) s += xT[j * nw + G * wpg + wq];
-    gs[G] = s;
-  }
-  __syncthreads();
-  const int lane = tid & 63, wave = tid >> 6;
-  // two rows per wavefront and pass: their plane words are requested together
-  for (int r0 = (blockIdx.x * kGemvWaves + wave) * 2; r0 < d_out; r0 += gridDim.x * kGemvWaves * 2) {
-    const bool two = r0 + 1 < d_out;
-    const int r1 = two ? r0 + 1 : r0;
-    float acc0 = 0.f, acc1 = 0.f;
-    for (int w = lane; w < nw; w += 64) {
-      uint32_t wa[K], wb[K];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int rows_per_pass = gridDim.x * kGemvWaves * 2;
+  for (int c0 = 0; c0 < d_in; c0 += kGemvChunk) {
+    const int cols = (d_in - c0 < kGemvChunk) ? d_in - c0 : kGemvChunk;
+    const int n_seg = cols / 4, n_word = cols / 32;
+    __syncthreads();                                     // the previous chunk's table is no longer read
+    for (int sgm = tid; sgm < n_seg; sgm += kGemvThreads) {
+      const float4 v = *reinterpret_cast<const float4*>(x + c0 + 4 * sgm);
+      float* t = T + sgm * kLutStride;
+      const float s01 = v.x + v.y, s23 = v.z + v.w;
+      t[0] = 0.f;        t[1] = v.x;         t[2] = v.y;         t[3] = s01;
+      t[4] = v.z;        t[5] = v.x + v.z;   t[6] = v.y + v.z;   t[7] = s01 + v.z;
+      t[8] = v.w;        t[9] = v.x + v.w;   t[10] = v.y + v.w;  t[11] = s01 + v.w;
+      t[12] = s23;       t[13] = v.x + s23;  t[14] = v.y + s23;  t[15] = s01 + s23;
+    }
+    __syncthreads();
+    for (int w = tid; w < n_word; w += kGemvThreads) {
+      float sw = 0.f;
 #pragma unroll
-      for (int i = 0; i < K; ++i) {
-        wa[i] = planes[((long)i * d_out + r0) * nw + w];
-        wb[i] = planes[((long)i * d_out + r1) * nw + w];
-      }
-      float ma[K], mb[K];
-#pragma unroll
-      for (int i = 0; i < K; ++i) ma[i] = mb[i] = 0.f;
-#pragma unroll
-      for (int j = 0; j < 32; ++j) {
-        const int xv = __builtin_bit_cast(int, xT[j * nw + w]);
+      for (int q = 0; q < 8; ++q) sw += T[(8 * w + q) * kLutStride + 15];
+      Sw[w] = sw;
+    }
+    __syncthreads();
+    const int w0 = c0 / 32;                              // first word of the chunk in a row
+    for (int r0 = (blockIdx.x * kGemvWaves + wave) * 2; r0 < d_out; r0 += rows_per_pass) {
+      const bool two = r0 + 1 < d_out;
+      const int r1 = two ? r0 + 1 : r0;
+      float acc0 = 0.f, acc1 = 0.f;
+      for (int w = lane; w < n_word; w += 64) {
+        uint32_t wa[K], wb[K];
 #pragma unroll
         for (int i = 0; i < K; ++i) {
-          // all-ones where the bit is set: the masked add needs no compare
-          ma[i] += __builtin_bit_cast(float, xv & __builtin_amdgcn_sbfe(static_cast<int>(wa[i]), j, 1));
-          mb[i] += __builtin_bit_cast(float, xv & __builtin_amdgcn_sbfe(static_cast<int>(wb[i]), j, 1));
+          wa[i] = planes[((long)i * d_out + r0) * nw + w0 + w];
+          wb[i] = planes[((long)i * d_out + r1) * nw + w0 + w];
+        }
+        const int G = (w0 + w) / wpg;
+        const float sw = Sw[w];
+        acc0 = fmaf((float)coefs[(long)r0 * n_grp + G], sw, acc0);
+        acc1 = fmaf((float)coefs[(long)r1 * n_grp + G], sw, acc1);
+        const float* tw = T + 8 * w * kLutStride;
+#pragma unroll
+        for (int i = 0; i < K; ++i) {
+          float ma = 0.f, mb = 0.f;
+#pragma unroll
+          for (int q = 0; q < 8; ++q) {
+            ma += tw[q * kLutStride + ((wa[i] >> (4 * q)) & 15u)];
+            mb += tw[q * kLutStride + ((wb[i] >> (4 * q)) & 15u)];
+          }
+          acc0 = fmaf((float)coefs[((long)(i + 1) * d_out + r0) * n_grp + G], ma, acc0);
+          acc1 = fmaf((float)coefs[((long)(i + 1) * d_out + r1) * n_grp + G], mb, acc1);
         }
       }
-      const int G = w / wpg;
 #pragma unroll
-      for (int i = 0; i < K; ++i) {
-        acc0 = fmaf((float)coefs[((long)(i + 1) * d_out + r0) * n_grp + G], ma[i], acc0);
-        acc1 = fmaf((float)coefs[((long)(i + 1) * d_out + r1) * n_grp + G], mb[i], acc1);
+      for (int o = 32; o > 0; o >>= 1) {
+        acc0 += __shfl_xor(acc0, o, 64);
+        acc1 += __shfl_xor(acc1, o, 64);
       }
-    }
-    for (int G = lane; G < n_grp; G += 64) {
-      acc0 = fmaf((float)coefs[(long)r0 * n_grp + G], gs[G], acc0);
-      acc1 = fmaf((float)coefs[(long)r1 * n_grp + G], gs[G], acc1);
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      acc0 += __shfl_xor(acc0, o, 64);
-      acc1 += __shfl_xor(acc1, o, 64);
-    }
-    if (lane == 0) {
-      y[r0] = acc0;
-      if (two) y[r1] = acc1;
+      if (lane == 0) {                                   // this wavefront owns these rows: no race
+        y[r0] = (c0 == 0 ? 0.f : y[r0]) + acc0;
+        if (two) y[r1] = (c0 == 0 ? 0.f : y[r1]) + acc1;
+      }
     }
   }
 }
@@ -94,21 +105,21 @@ extern "C" int bpdq_gemv(const uint32_t* planes, const uint16_t* coefs_h, int d_
   if (!planes) return -1;
   if (!coefs_h || (reinterpret_cast<uintptr_t>(coefs_h) & 1)) return -2;
   if (d_out <= 0) return -3;
-  if (d_in <= 0 || d_in % 32 || d_in > kGemvMaxDin) return -4;
+  if (d_in <= 0 || d_in % 32) return -4;
   if (bits < 1 || bits > 4) return -5;
   if (group < 32 || group % 32 || d_in % group) return -6;
-  if (!x) return -7;
+  if (!x || (reinterpret_cast<uintptr_t>(x) & 15)) return -7;
   if (!y) return -8;
-  const size_t lds = (size_t)(d_in + d_in / group) * sizeof(float);
+  const size_t lds = kGemvLdsBytes;
   const _Float16* ch = reinterpret_cast<const _Float16*>(coefs_h);
   int grid = bpdq_ceil_div(d_out, kGemvWaves * 2);   // 2 rows per wavefront and pass
-  if (grid > 256) grid = 256;                        // one work-group per CU; each stages x once
+  if (grid > 256) grid = 256;                        // one work-group per CU; each builds the table once
   auto launch = [&](auto kern) -> int {
     static bool attr_set = false;
     if (!attr_set) {
       BPDQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)((kGemvMaxDin + kGemvMaxDin / 32) * sizeof(float))));
+                                       (int)kGemvLdsBytes));
       attr_set = true;
     }
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kGemvThreads), lds, stream, planes, ch, d_out, d_in, group, x, y);
