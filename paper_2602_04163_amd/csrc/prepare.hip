@@ -153,21 +153,63 @@ __device__ __forceinline__ void factor64(double (&a)[4][4], double (*sR)[NB + 1]
   __syncthreads();
 }
 
-// Row `row` of the tile sX: x R^T = a by substitution from the last column: x_j = rem_j / R_jj,
-// then rem_k -= x_j R[k][j] for every k < j (independent updates: no serial dot product).
-__device__ __forceinline__ void trsm_row(double (*sX)[NB + 1], int row, const double (*sR)[NB + 1],
-                                         const double* sInvD) {
-  double x[NB];
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+
+// X R^T = A for one or two 64 x 64 tiles at once, in place, by blocks of 16 columns from the
+// right (R upper, sInvD[j] = 1 / R_jj):
+//   (1) inside a block: substitution, one lane per row (wavefront 0 takes sXa, wavefront 1 sXb);
+//   (2) the blocks to its left receive  A_J' -= X_J R[J', J]^T  on the fp64 matrix cores
+//       (v_mfma_f64_16x16x4_f64; wavefront w takes rows 16 w .. 16 w + 15 of both tiles).
+// A quarter of the dependent multiply-adds of a plain substitution stay on the critical path.
+// All 256 threads call this; it ends with a barrier.
+__device__ __forceinline__ void trsm_block_subst(double (*sX)[NB + 1], int row, int J,
+                                                 const double (*sR)[NB + 1], const double* sInvD) {
+  double x[16];
 #pragma unroll
-  for (int j = 0; j < NB; ++j) x[j] = sX[row][j];
+  for (int c = 0; c < 16; ++c) x[c] = sX[row][16 * J + c];
 #pragma unroll
-  for (int j = NB - 1; j >= 0; --j) {
-    x[j] *= sInvD[j];
+  for (int c = 15; c >= 0; --c) {
+    x[c] *= sInvD[16 * J + c];
 #pragma unroll
-    for (int k = 0; k < j; ++k) x[k] = fma(-x[j], sR[k][j], x[k]);
+    for (int k = 0; k < c; ++k) x[k] = fma(-x[c], sR[16 * J + k][16 * J + c], x[k]);
   }
 #pragma unroll
-  for (int j = 0; j < NB; ++j) sX[row][j] = x[j];
+  for (int c = 0; c < 16; ++c) sX[row][16 * J + c] = x[c];
+}
+
+__device__ __forceinline__ void trsm_block_update(double (*sX)[NB + 1], int J,
+                                                  const double (*sR)[NB + 1]) {
+  const int lane = threadIdx.x & 63, i0 = 16 * (threadIdx.x >> 6);
+  const int lm = lane & 15, lq = lane >> 4;
+  double a[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) a[ks] = sX[i0 + lm][16 * J + 4 * ks + lq];      // A[m][k] = X_J
+  for (int Jp = 0; Jp < J; ++Jp) {
+    f64x4 acc = (f64x4){0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const double b = sR[16 * Jp + lm][16 * J + 4 * ks + lq];                    // B[k][n] = R[J'n][Jk]
+      acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a[ks], b, acc, 0, 0, 0);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) sX[i0 + 4 * r + lq][16 * Jp + lm] -= acc[r];       // D[4r + l/16][l%16]
+  }
+}
+
+__device__ __forceinline__ void trsm64_blocked(double (*sXa)[NB + 1], double (*sXb)[NB + 1], bool two,
+                                               const double (*sR)[NB + 1], const double* sInvD) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+#pragma unroll 1
+  for (int J = NB / 16 - 1; J >= 0; --J) {
+    if (w == 0) trsm_block_subst(sXa, lane, J, sR, sInvD);
+    else if (w == 1 && two) trsm_block_subst(sXb, lane, J, sR, sInvD);
+    __syncthreads();
+    if (J > 0) {
+      trsm_block_update(sXa, J, sR);
+      if (two) trsm_block_update(sXb, J, sR);
+    }
+    __syncthreads();
+  }
 }
 
 // The symmetric 64 x 64 block at (p0, p0) into the register tiling of factor64 (only the upper
@@ -222,8 +264,7 @@ __global__ __launch_bounds__(256) void panel_factor_kernel(double* __restrict__ 
     if (tid == 0) *pair_flag = 0;
   }
   if (n_above == 0) return;
-  if (tid < NB) trsm_row(sA, tid, sR, sInvD);
-  __syncthreads();
+  trsm64_blocked(sA, sA, false, sR, sInvD);
   for (int e = tid; e < NB * NB; e += 256) {
     const int i = e / NB, j = e % NB;
     if (r0 + i < p0 && j < nb) A[(long)(r0 + i) * d + p0 + j] = sA[i][j];
@@ -275,8 +316,6 @@ __global__ __launch_bounds__(64) void diag_inverse_kernel(const double* __restri
 //   D: register r of lane l is D[4 * r + l / 16][l % 16].
 // sa is [m][k]; sb is [k][n], or [n][k] when B_T (second operand given by rows, as in a SYRK).
 // With the 65-double row pitch every 16-lane group reads 16 distinct bank pairs.
-typedef double f64x4 __attribute__((ext_vector_type(4)));
-
 struct Quad64 {
   f64x4 c[2][2];
 };
@@ -376,10 +415,9 @@ __global__ __launch_bounds__(256) void panel_pair_kernel(double* __restrict__ A,
   factor64(a, sR, col, sInvD, info, p2, first);
   if (first)
     for (int e = tid; e < NB * NB; e += 256) Rdiag2[e] = sR[e / NB][e % NB];
-  // R12 = D12 R22^-T (wavefront 0) and X2 = A2 R22^-T (wavefront 1), one thread per row
-  if (tid < NB) trsm_row(sR12, tid, sR, sInvD);
-  else if (tid < 2 * NB && n_above > 0) trsm_row(sA2, tid - NB, sR, sInvD);
-  __syncthreads();
+  // R12 = D12 R22^-T and X2 = A2 R22^-T
+  __syncthreads();                                  // Rdiag2 has been read out of sR
+  trsm64_blocked(sR12, sA2, n_above > 0, sR, sInvD);
   {
     Quad64 q;
     quad_zero(q);
@@ -408,8 +446,7 @@ __global__ __launch_bounds__(256) void panel_pair_kernel(double* __restrict__ A,
     }
   }
   if (n_above == 0) return;
-  if (tid < NB) trsm_row(sA1, tid, sR, sInvD);
-  __syncthreads();
+  trsm64_blocked(sA1, sA1, false, sR, sInvD);
   for (int e = tid; e < NB * NB; e += 256) {
     const int i = e / NB, j = e % NB;
     if (r0 + i < p1) {
