@@ -122,25 +122,29 @@ __device__ __forceinline__ void factor64(double (&a)[4][4], double (*sR)[NB + 1]
         for (int r = 0; r < 4; ++r) cbuf[4 * ty + r] = a[r][jj];
       }
       __syncthreads();
-      double piv = cbuf[j];
-      if (!(piv > 0.0)) {
-        if (tid == 0 && report) atomicCAS(info, 0, p0 + j + 1);
-        piv = 1.0;
-      }
-      const double ip = fast_rcp(piv);
+      // every LDS read of the step is issued before the first is used: one round trip, not three
+      const double piv_raw = cbuf[j];
       double ci[4], cj[4];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) ci[r] = cbuf[4 * ty + r] * ip;
+      for (int r = 0; r < 4; ++r) ci[r] = cbuf[4 * ty + r];
 #pragma unroll
       for (int c = 0; c < 4; ++c) cj[c] = cbuf[4 * tx + c];
+      const double mine = cbuf[tid & (NB - 1)];
+      const bool bad = !(piv_raw > 0.0);
+      const double piv = bad ? 1.0 : piv_raw;
+      const double ip = fast_rcp(piv);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) ci[r] *= ip;
 #pragma unroll
       for (int r = 0; r < 4; ++r)
 #pragma unroll
         for (int c = 0; c < 4; ++c) a[r][c] = fma(-ci[r], cj[c], a[r][c]);
+      // off the critical chain: the finished column (unscaled; scaled after the loop), the pivot
       if (tid < NB) {
-        sR[tid][j] = (tid <= j) ? cbuf[tid] : 0.0;     // unscaled column; scaled after the loop
+        sR[tid][j] = (tid <= j) ? mine : 0.0;
         if (tid == j) sInvD[j] = piv;
       }
+      if (bad && tid == 0 && report) atomicCAS(info, 0, p0 + j + 1);
     }
   }
   __syncthreads();
