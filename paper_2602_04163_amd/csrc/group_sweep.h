@@ -33,6 +33,10 @@ constexpr int kSweepThreads = 256;
 // registers per lane; the state of a g = 256 group does not fit that.
 template <int G>
 constexpr int kSweepWavesPerSimd = (G <= 128) ? 2 : 1;
+// The lazy block update rides along with the sweep (extra work-groups of the group launch) only
+// where a sweeping and an updating work-group fit on one CU; at g = 256 it is a launch of its own.
+template <int G>
+constexpr bool kTailInSweep = (G <= 128);
 
 // ------------------------------------------------------------------ lane helpers -----------
 template <int CTRL>
@@ -264,20 +268,54 @@ __device__ __forceinline__ void run_columns(RowState<K, G>& st, const float* sU,
 }
 
 // Stage the local factor U[s0:s0+G, s0:s0+G] in LDS (layout above) and 1 / U_ll in sInv.
+// The G x G block is fetched as float4 with up to 16 loads of a thread in flight at once (a rolled
+// element loop would wait for memory once per element); the part on or below the diagonal of a
+// kept slot is stored as zero.
 template <int G>
 __device__ __forceinline__ void stage_local_factor(const float* __restrict__ U, int ldu, int s0,
                                                    float* sU, float* sInv) {
   using Lay = SuLayout<G>;
-  for (int e = threadIdx.x; e < G * G; e += kSweepThreads) {
-    const int l = e / G, j = e % G;
-    const int M = l >> 4, m = j >> 4;
-    if (m >= M) {
-      const float v = U[(long)(s0 + l) * ldu + s0 + j];
-      int off = 0;
-      for (int q = 0; q < M; ++q) off += 256 * Lay::live(q);
-      off += 16 * (l & 15) * Lay::live(M);
-      sU[off + Lay::slot_index(Lay::live(M), m - M, j & 15)] = (j > l) ? v : 0.f;
-      if (j == l) sInv[l] = 1.0f / v;
+  constexpr int CPL = G / 16;
+  if constexpr (G >= 256) {
+    // the g = 256 kernels are at the limit of what the compiler handles in reasonable time:
+    // they keep the plain element loop
+    for (int e = threadIdx.x; e < G * G; e += kSweepThreads) {
+      const int l = e / G, j = e % G;
+      const int M = l >> 4, m = j >> 4;
+      if (m >= M) {
+        const float v = U[(long)(s0 + l) * ldu + s0 + j];
+        const int off = 256 * (M * CPL - M * (M - 1) / 2) + 16 * (l & 15) * Lay::live(M);
+        sU[off + Lay::slot_index(Lay::live(M), m - M, j & 15)] = (j > l) ? v : 0.f;
+        if (j == l) sInv[l] = 1.0f / v;
+      }
+    }
+    return;
+  }
+  constexpr int kPer = G * G / 4 / kSweepThreads;        // float4 loads per thread: 1, 4, 16
+  constexpr int kBatch = kPer < 16 ? kPer : 16;
+  for (int b = 0; b < kPer; b += kBatch) {
+    float4 v[kBatch];
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int q = threadIdx.x + (b + u) * kSweepThreads;
+      const int l = q / (G / 4), j4 = (q % (G / 4)) * 4;
+      v[u] = *reinterpret_cast<const float4*>(U + (long)(s0 + l) * ldu + s0 + j4);
+    }
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int q = threadIdx.x + (b + u) * kSweepThreads;
+      const int l = q / (G / 4), j4 = (q % (G / 4)) * 4;
+      const int M = l >> 4, m = j4 >> 4;                  // the four columns share one slot
+      if (m >= M) {
+        const int off = 256 * (M * CPL - M * (M - 1) / 2) + 16 * (l & 15) * Lay::live(M);
+        const float e[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const int j = j4 + c;
+          sU[off + Lay::slot_index(Lay::live(M), m - M, j & 15)] = (j > l) ? e[c] : 0.f;
+          if (j == l) sInv[l] = 1.0f / e[c];
+        }
+      }
     }
   }
 }
@@ -414,9 +452,19 @@ __device__ __forceinline__ void tail_role(const TailArgs& ta, const float* __res
   const int r0 = tm * TailGemm::kTileM, c0 = ta.c_begin + tn * TailGemm::kTileN;
   float* Wp = ta.Wp;
   const int c_end = ta.c_end;
+  // in-place read-modify-write of this lane's 64 results: all loads first (masked elements read
+  // a valid address and are not stored), then the stores
+  float old[TailGemm::kAccPerLane];
+  int n = 0;
+  TailGemm::for_each(acc, [&](int row, int col, float) {
+    const int r = r0 + row, c = c0 + col;
+    old[n++] = Wp[(r < d_out && c < c_end) ? (long)r * ldw + c : 0L];
+  });
+  n = 0;
   TailGemm::for_each(acc, [&](int row, int col, float v) {
     const int r = r0 + row, c = c0 + col;
-    if (r < d_out && c < c_end) Wp[(long)r * ldw + c] -= v;
+    if (r < d_out && c < c_end) Wp[(long)r * ldw + c] = old[n] - v;
+    ++n;
   });
 }
 
@@ -451,10 +499,13 @@ __device__ __forceinline__ void pending_update_tile(const float* __restrict__ Ea
       float a[kChunk], bv[kChunk][BPW];
 #pragma unroll
       for (int u = 0; u < kChunk; ++u) {
+        // steps past Kp re-read step k (a valid address) and contribute nothing
         const bool in = k + 4 * u < Kp;
-        a[u] = in ? ap[(long)(k + 4 * u) * lde] : 0.f;
+        const long kk = in ? k + 4 * u : k;
+        const float av = ap[kk * lde];
+        a[u] = in ? av : 0.f;
 #pragma unroll
-        for (int b = 0; b < BPW; ++b) bv[u][b] = in ? bp[(long)(k + 4 * u) * ldu + 16 * b] : 0.f;
+        for (int b = 0; b < BPW; ++b) bv[u][b] = bp[kk * ldu + 16 * b];
       }
 #pragma unroll
       for (int u = 0; u < kChunk; ++u)
@@ -538,9 +589,11 @@ __global__ __launch_bounds__(kSweepThreads, kSweepWavesPerSimd<G>) void bpdq_gro
     float* __restrict__ cand_coef,
     float* __restrict__ cand_E, double* __restrict__ cand_score, int n_wg,
     const float* __restrict__ Eall, int lde, int kp0, TailArgs ta) {
-  if ((int)blockIdx.x >= ta.first_wg) {
-    tail_role(ta, U, ldu, lde, ldw, d_out);
-    return;
+  if constexpr (kTailInSweep<G>) {
+    if ((int)blockIdx.x >= ta.first_wg) {
+      tail_role(ta, U, ldu, lde, ldw, d_out);
+      return;
+    }
   }
   constexpr int CPL = G / 16;
   extern __shared__ float lds[];
@@ -618,9 +671,11 @@ __global__ __launch_bounds__(kSweepThreads, kSweepWavesPerSimd<G>) void uniform_
     int coef_fp16, unsigned char* __restrict__ cand_codes, float* __restrict__ cand_coef,
     float* __restrict__ cand_E, double* __restrict__ cand_score, int n_wg,
     const float* __restrict__ Eall, int lde, int kp0, TailArgs ta) {
-  if ((int)blockIdx.x >= ta.first_wg) {
-    tail_role(ta, U, ldu, lde, ldw, d_out);
-    return;
+  if constexpr (kTailInSweep<G>) {
+    if ((int)blockIdx.x >= ta.first_wg) {
+      tail_role(ta, U, ldu, lde, ldw, d_out);
+      return;
+    }
   }
   constexpr int CPL = G / 16;
   extern __shared__ float lds[];
@@ -794,6 +849,10 @@ static inline QuantLayout quant_layout(int d_out, int d_in, const bpdq_params& p
   return L;
 }
 
+// the tail role as a kernel of its own (defined with the host loop)
+int launch_tail_update(hipStream_t stream, TailArgs ta, const float* U, int ldu, int lde, int ldw,
+                       int d_out, int n_tiles);
+
 // One group: the sweep kernel (with the pending updates read left-looking from column kp0 on, and
 // the tail role `ta` for the previous block, see above), then selection + commit.
 template <int K, int G>
@@ -820,7 +879,12 @@ static inline int launch_group(hipStream_t stream, const float* Wp, int d_out, i
   const bool uniform = (p.grid == BPDQ_GRID_UNIFORM);
   const int T = uniform ? 0 : p.refine_iters;
   ta.first_wg = L.n_wg;
-  const int n_tail = ta.tiles_n > 0 ? bpdq_ceil_div(L.lde, TailGemm::kTileM) * ta.tiles_n : 0;
+  int n_tail = ta.tiles_n > 0 ? bpdq_ceil_div(L.lde, TailGemm::kTileM) * ta.tiles_n : 0;
+  if (!kTailInSweep<G> && n_tail > 0) {
+    const int rc = launch_tail_update(stream, ta, U, d_in, L.lde, d_in, d_out, n_tail);
+    if (rc) return rc;
+    n_tail = 0;
+  }
   const dim3 grid(L.n_wg + n_tail);
   if (uniform) {
     hipLaunchKernelGGL((uniform_group_kernel<K, G>), grid, dim3(kSweepThreads), lds, stream,

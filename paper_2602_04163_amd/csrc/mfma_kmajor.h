@@ -44,6 +44,7 @@ struct KMajorGemm {
   struct Acc {
     f32x16 c[TI][TJ];
   };
+  static constexpr int kAccPerLane = TI * TJ * 16;             // accumulator values per lane
 
   __device__ static __forceinline__ void zero(Acc& acc) {
 #pragma unroll

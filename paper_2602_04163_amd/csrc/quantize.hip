@@ -5,6 +5,29 @@
 
 namespace bpdq {
 
+// The lazy block update as a launch of its own (group sizes whose sweep kernel cannot share a CU
+// with it): the same tail role, one 128 x 128 tile per work-group.
+__global__ __launch_bounds__(TailGemm::kThreads) void tail_update_kernel(TailArgs ta, const float* __restrict__ U,
+                                                                         int ldu, int lde, int ldw, int d_out) {
+  tail_role(ta, U, ldu, lde, ldw, d_out);
+}
+
+int launch_tail_update(hipStream_t stream, TailArgs ta, const float* U, int ldu, int lde, int ldw,
+                       int d_out, int n_tiles) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    BPDQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(tail_update_kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)TailGemm::kLdsBytes));
+    attr_set = true;
+  }
+  ta.first_wg = 0;
+  hipLaunchKernelGGL(tail_update_kernel, dim3(n_tiles), dim3(TailGemm::kThreads), TailGemm::kLdsBytes,
+                     stream, ta, U, ldu, lde, ldw, d_out);
+  BPDQ_LAUNCH_CHECK();
+  return 0;
+}
+
 // working copy of W with dead input channels zeroed
 __global__ __launch_bounds__(256) void copy_in_kernel(const float* __restrict__ W, long n, int d_in,
                                                       const unsigned char* __restrict__ dead,
