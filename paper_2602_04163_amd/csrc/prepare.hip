@@ -275,42 +275,50 @@ __global__ __launch_bounds__(256) void panel_factor_kernel(double* __restrict__ 
   }
 }
 
-// Inverses of all diagonal blocks of R at once (one work-group per block, thread c solves
+// Inverses of all diagonal blocks of R at once (one work-group per block, thread c < 64 solves
 // R x = e_c by back substitution); the inverse replaces the diagonal block of A (upper part,
 // zeros below), which until now still held the unfactored block.  A block that was the second of
 // a panel pair also brings its R12 (rows of the block before it) from the side buffer into A.
-__global__ __launch_bounds__(64) void diag_inverse_kernel(const double* __restrict__ Rdiag,
-                                                          const double* __restrict__ R12buf,
-                                                          const int* __restrict__ pair_flag,
-                                                          double* __restrict__ A, int d) {
+__global__ __launch_bounds__(256) void diag_inverse_kernel(const double* __restrict__ Rdiag,
+                                                           const double* __restrict__ R12buf,
+                                                           const int* __restrict__ pair_flag,
+                                                           double* __restrict__ A, int d) {
   __shared__ double s[NB][NB + 1];
   __shared__ double x[NB][NB + 1];
   const int p0 = blockIdx.x * NB;
   const int nb = (d - p0 < NB) ? d - p0 : NB;
-  const int c = threadIdx.x;
+  const int tid = threadIdx.x;
   const double* src = Rdiag + (long)blockIdx.x * NB * NB;
-  for (int e = c; e < NB * NB; e += 64) {
-    s[e / NB][e % NB] = src[e];
-    x[e / NB][e % NB] = 0.0;
+  const bool pair = pair_flag[blockIdx.x] != 0;
+  {
+    double v[16], r12[16];
+    fetch_tile64(src, [](int, int) { return true; }, [](int i, int j) { return (long)i * NB + j; }, v);
+    if (pair)
+      fetch_tile64(R12buf + (long)blockIdx.x * NB * NB, [](int, int) { return true; },
+                   [](int i, int j) { return (long)i * NB + j; }, r12);
+    put_tile64(s, v);
+#pragma unroll
+    for (int t = 0; t < 16; ++t) {
+      const int e = tid + 256 * t;
+      const int i = e >> 6, j = e & 63;
+      x[i][j] = 0.0;
+      if (pair && j < nb) A[(long)(p0 - NB + i) * d + p0 + j] = r12[t];
+    }
   }
   __syncthreads();
-  x[c][c] = 1.0 / s[c][c];
-  for (int i = c - 1; i >= 0; --i) {
-    double acc = 0.0;
-    for (int m = i + 1; m <= c; ++m) acc += s[i][m] * x[m][c];
-    x[i][c] = -acc / s[i][i];
+  if (tid < NB) {
+    const int c = tid;
+    x[c][c] = 1.0 / s[c][c];
+    for (int i = c - 1; i >= 0; --i) {
+      double acc = 0.0;
+      for (int m = i + 1; m <= c; ++m) acc += s[i][m] * x[m][c];
+      x[i][c] = -acc / s[i][i];
+    }
   }
   __syncthreads();
-  for (int e = c; e < NB * NB; e += 64) {
+  for (int e = tid; e < NB * NB; e += 256) {
     const int i = e / NB, j = e % NB;
     if (i < nb && j < nb) A[(long)(p0 + i) * d + p0 + j] = (j >= i) ? x[i][j] : 0.0;
-  }
-  if (pair_flag[blockIdx.x]) {
-    const double* r12 = R12buf + (long)blockIdx.x * NB * NB;
-    for (int e = c; e < NB * NB; e += 64) {
-      const int i = e / NB, j = e % NB;
-      if (j < nb) A[(long)(p0 - NB + i) * d + p0 + j] = r12[e];
-    }
   }
 }
 
@@ -713,7 +721,7 @@ extern "C" int bpdq_prepare(const float* H, int d_in, float damp, float* U, unsi
     }
   }
 
-  hipLaunchKernelGGL(diag_inverse_kernel, dim3(P), dim3(64), 0, stream, Rdiag, R12buf, pair_flag, A, d);
+  hipLaunchKernelGGL(diag_inverse_kernel, dim3(P), dim3(256), 0, stream, Rdiag, R12buf, pair_flag, A, d);
   BPDQ_LAUNCH_CHECK();
   const int depth = tree_depth(P);
   for (int dd = depth - 1; dd >= 0; --dd) {
