@@ -37,7 +37,7 @@ extern "C" {
  * alpha = 1e-4). */
 typedef struct bpdq_params {
   int   bits;           /* k, number of bit-planes: 1..4                                      */
-  int   group;          /* g: 32, 64, 128 or 256; must divide d_in                            */
+  int   group;          /* g: 32, 64, 128 or 256 (256 only with bits <= 3); must divide d_in  */
   int   block;          /* lazy-update block B; the effective block is max(B, g); g | B       */
   int   refine_iters;   /* T >= 0 iterations of (bit-plane update, refit, delta correction);
                            0 keeps the initialisation + one fit (Sec. 3.2)                    */

@@ -853,6 +853,50 @@ static inline QuantLayout quant_layout(int d_out, int d_in, const bpdq_params& p
 int launch_tail_update(hipStream_t stream, TailArgs ta, const float* U, int ldu, int lde, int ldw,
                        int d_out, int n_tiles);
 
+template <int G>
+constexpr size_t sweep_lds_bytes() {
+  const size_t a = (size_t)(SuLayout<G>::floats() + G + 2 * kRowsPerWG + PendingTile<G>::kFloats) * sizeof(float);
+  return a < TailGemm::kLdsBytes ? TailGemm::kLdsBytes : a;
+}
+
+// launch of the fixed-grid comparator's sweep kernel
+struct UniformSweepArgs {
+  hipStream_t stream;
+  int grid;
+  const float* Wp;
+  int d_in, d_out;
+  const float* U;
+  int s0, coef_fp16;
+  unsigned char* c_codes;
+  float* c_coef;
+  float* c_E;
+  double* c_score;
+  int n_wg;
+  const float* Eall;
+  int lde, kp0;
+  TailArgs ta;
+};
+
+template <int K, int G>
+static inline int launch_uniform_sweep(const UniformSweepArgs& a) {
+  const size_t lds = sweep_lds_bytes<G>();
+  static bool attr_set = false;
+  if (!attr_set) {
+    BPDQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(uniform_group_kernel<K, G>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((uniform_group_kernel<K, G>), dim3(a.grid), dim3(kSweepThreads), lds, a.stream,
+                     a.Wp, a.d_in, a.d_out, a.U, a.d_in, a.s0, a.coef_fp16, a.c_codes, a.c_coef, a.c_E,
+                     a.c_score, a.n_wg, a.Eall, a.lde, a.kp0, a.ta);
+  BPDQ_LAUNCH_CHECK();
+  return 0;
+}
+// group size 256: defined in group_sweep_k{K}_g256u.hip (the two g = 256 kernels of a plane count
+// are the longest compilations of the build; apart they run in parallel)
+template <int K>
+int launch_uniform_sweep_256(const UniformSweepArgs& a);
+
 // One group: the sweep kernel (with the pending updates read left-looking from column kp0 on, and
 // the tail role `ta` for the previous block, see above), then selection + commit.
 template <int K, int G>
@@ -865,16 +909,7 @@ static inline int launch_group(hipStream_t stream, const float* Wp, int d_out, i
   float* c_E = reinterpret_cast<float*>(base + L.e_off);
   double* c_score = reinterpret_cast<double*>(base + L.score_off);
   float* Eall = reinterpret_cast<float*>(base + L.eall_off);
-  size_t lds = (size_t)(SuLayout<G>::floats() + G + 2 * kRowsPerWG + PendingTile<G>::kFloats) * sizeof(float);
-  if (lds < TailGemm::kLdsBytes) lds = TailGemm::kLdsBytes;
-  static bool attr_set = false;
-  if (!attr_set) {
-    BPDQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(bpdq_group_kernel<K, G>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    BPDQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(uniform_group_kernel<K, G>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    attr_set = true;
-  }
+  const size_t lds = sweep_lds_bytes<G>();
   const int gi = s0 / G;
   const bool uniform = (p.grid == BPDQ_GRID_UNIFORM);
   const int T = uniform ? 0 : p.refine_iters;
@@ -885,13 +920,22 @@ static inline int launch_group(hipStream_t stream, const float* Wp, int d_out, i
     if (rc) return rc;
     n_tail = 0;
   }
-  const dim3 grid(L.n_wg + n_tail);
+  const int grid = L.n_wg + n_tail;
   if (uniform) {
-    hipLaunchKernelGGL((uniform_group_kernel<K, G>), grid, dim3(kSweepThreads), lds, stream,
-                       Wp, d_in, d_out, U, d_in, s0, p.coef_fp16, c_codes, c_coef, c_E, c_score, L.n_wg, Eall,
-                       L.lde, kp0, ta);
+    const UniformSweepArgs a{stream, grid, Wp, d_in, d_out, U, s0, p.coef_fp16, c_codes, c_coef, c_E,
+                             c_score, L.n_wg, Eall, L.lde, kp0, ta};
+    int rc;
+    if constexpr (G >= 256) rc = launch_uniform_sweep_256<K>(a);   // a translation unit of its own
+    else rc = launch_uniform_sweep<K, G>(a);
+    if (rc) return rc;
   } else {
-    hipLaunchKernelGGL((bpdq_group_kernel<K, G>), grid, dim3(kSweepThreads), lds, stream,
+    static bool attr_set = false;
+    if (!attr_set) {
+      BPDQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(bpdq_group_kernel<K, G>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+      attr_set = true;
+    }
+    hipLaunchKernelGGL((bpdq_group_kernel<K, G>), dim3(grid), dim3(kSweepThreads), lds, stream,
                        Wp, d_in, d_out, U, d_in, s0, T, p.alpha, p.coef_fp16, c_codes, c_coef, c_E, c_score,
                        L.n_wg, Eall, L.lde, kp0, ta);
   }
@@ -908,8 +952,9 @@ typedef int (*GroupLauncher)(hipStream_t, const float*, int, int, const float*, 
                              float*, float*, double*, int*);
 
 // The group kernels are large, fully unrolled kernels: one translation unit per plane count
-// instantiates group sizes 32 / 64 / 128, and one more per plane count group size 256, which
-// keeps the build parallel.
+// instantiates group sizes 32 / 64 / 128, and two more per plane count (1..3) group size 256
+// (variable grid, fixed grid), which keeps the build parallel.  Four planes at g = 256 -- a
+// combination the paper does not use -- would by itself double the build time and is left out.
 GroupLauncher pick_group_k1(int g);
 GroupLauncher pick_group_k2(int g);
 GroupLauncher pick_group_k3(int g);
@@ -917,7 +962,6 @@ GroupLauncher pick_group_k4(int g);
 GroupLauncher group256_k1();
 GroupLauncher group256_k2();
 GroupLauncher group256_k3();
-GroupLauncher group256_k4();
 
 template <int K>
 static inline GroupLauncher pick_group_g(int g) {

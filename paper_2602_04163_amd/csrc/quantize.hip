@@ -97,6 +97,7 @@ static int check_params(int d_out, int d_in, const bpdq_params* p) {
   if (!p) return 1;
   if (p->bits < 1 || p->bits > 4) return 1;
   if (p->group != 32 && p->group != 64 && p->group != 128 && p->group != 256) return 1;
+  if (p->group == 256 && p->bits > 3) return 1;      // 4 planes at g = 256 are not built (see header)
   if (d_in % p->group || d_in % 32) return 1;
   const int B = p->block > p->group ? p->block : p->group;
   if (p->block < 1 || B % p->group) return 1;
@@ -114,7 +115,6 @@ static GroupLauncher pick_group(int k, int g) {
       case 1: return group256_k1();
       case 2: return group256_k2();
       case 3: return group256_k3();
-      case 4: return group256_k4();
     }
     return nullptr;
   }

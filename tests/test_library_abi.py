@@ -54,6 +54,9 @@ def test_size_queries(lib):
     assert binding.bpdq_quantize_workspace_bytes(3584, 3584, bad) == 0
     assert binding.bpdq_quantize_workspace_bytes(3584, 3584, binding.make_params(2, 128, 128, 5, coef_fp16=True)) == need
     assert binding.bpdq_quantize_workspace_bytes(8192, 8192, binding.make_params(2, 256, 128, 10)) > 0
+    # four planes at group size 256 are not built
+    assert binding.bpdq_quantize_workspace_bytes(8192, 8192, binding.make_params(4, 256, 256, 5)) == 0
+    assert binding.bpdq_quantize_workspace_bytes(8192, 8192, binding.make_params(4, 128, 128, 5)) > 0
     assert binding.bpdq_prepare_workspace_bytes(3584) >= 3584 * 3584 * 8
     assert binding.bpdq_hessian_workspace_bytes(0, 3584) == 0
     # a full 262144-token call on a 3584-wide layer is split over the token axis
