@@ -94,8 +94,10 @@ int bpdq_prepare(const float* H, int d_in, float damp, float* U, unsigned char* 
  * refine_iters times: column-wise nearest-level bit-plane update with error propagation
  * (Eq. 3-4, 7-8), coefficient refit, delta correction (Eq. 9); the iterate with the smallest
  * ||E_group||_F^2 is kept (the initial state counts as iterate 0; ties keep the earliest).
- * Its propagation error is applied to the rest of the block at once and to all later
- * columns by one GEMM per block (W'[:, end:] -= E_blk U[blk, end:]).
+ * Its propagation error reaches the columns not yet quantized exactly as
+ * W'[:, end:] -= E_blk U[blk, end:] per block (and E* U[grp, rest of block] inside a block):
+ * one GEMM per block for the far columns, applied one block late and overlapped with the next
+ * sweep, while the groups of the next block read the pending terms directly from the kept E*.
  *   W       : d_out x d_in, read only.
  *   U, dead : from bpdq_prepare (dead may be NULL).
  *   planes  : uint32 [bits][d_out][d_in/32]; column c of plane B_i (i = 1..bits) is bit
