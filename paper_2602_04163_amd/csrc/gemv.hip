@@ -8,8 +8,10 @@
 // instead of 32 masked adds.  The table of a chunk of up to 8192 columns (136 KB of LDS with
 // its padding) is built once per work-group and chunk -- 15 adds per segment -- and used by all
 // its rows.  One wavefront owns a pair of rows for the whole call (16 wavefronts per work-group,
-// one work-group per CU); lane l takes the 32-column words l, l + 64, ... of the chunk.  The row
-// stride of the table is 17 floats so that lanes with different nibbles fall into different banks.
+// one work-group per CU); lane l takes the 32-column words l, l + 64, ... of the chunk.  The table
+// is laid out T[q][nibble][w] (q = nibble position inside a word, w = word, fastest): the 64 lanes
+// of a wavefront hold consecutive words, so whatever their nibbles are they fall into consecutive
+// banks -- two lanes per bank, the minimum for 64 lanes.
 #include "common.h"
 
 namespace bpdq {
@@ -17,8 +19,8 @@ namespace bpdq {
 constexpr int kGemvThreads = 1024;
 constexpr int kGemvWaves = kGemvThreads / 64;
 constexpr int kGemvChunk = 8192;                  // columns per table
-constexpr int kLutStride = 17;
-constexpr size_t kGemvLdsBytes = (size_t)((kGemvChunk / 4) * kLutStride + kGemvChunk / 32) * sizeof(float);
+constexpr int kChunkWords = kGemvChunk / 32;      // 256: the word stride of the table, also for a short last chunk
+constexpr size_t kGemvLdsBytes = (size_t)(8 * 16 * kChunkWords + kChunkWords) * sizeof(float);
 
 template <int K>
 __global__ __launch_bounds__(kGemvThreads) void gemv_planes_kernel(const uint32_t* __restrict__ planes,
@@ -27,29 +29,30 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_planes_kernel(const uint32_
                                                                    const float* __restrict__ x,
                                                                    float* __restrict__ y) {
   extern __shared__ float lds[];
-  float* T = lds;                                        // [segments of the chunk][17]
-  float* Sw = lds + (kGemvChunk / 4) * kLutStride;       // sum of x over each word of the chunk
+  float* T = lds;                                        // [8][16][kChunkWords]
+  float* Sw = lds + 8 * 16 * kChunkWords;                // sum of x over each word of the chunk
   const int nw = d_in / 32, n_grp = d_in / group, wpg = group / 32;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int rows_per_pass = gridDim.x * kGemvWaves * 2;
   for (int c0 = 0; c0 < d_in; c0 += kGemvChunk) {
     const int cols = (d_in - c0 < kGemvChunk) ? d_in - c0 : kGemvChunk;
-    const int n_seg = cols / 4, n_word = cols / 32;
+    const int n_word = cols / 32;
     __syncthreads();                                     // the previous chunk's table is no longer read
-    for (int sgm = tid; sgm < n_seg; sgm += kGemvThreads) {
-      const float4 v = *reinterpret_cast<const float4*>(x + c0 + 4 * sgm);
-      float* t = T + sgm * kLutStride;
+    for (int sgm = tid; sgm < 8 * n_word; sgm += kGemvThreads) {
+      const int q = sgm / n_word, w = sgm % n_word;      // consecutive threads: consecutive words
+      const float4 v = *reinterpret_cast<const float4*>(x + c0 + 32 * w + 4 * q);
+      float* t = T + q * 16 * kChunkWords + w;
       const float s01 = v.x + v.y, s23 = v.z + v.w;
-      t[0] = 0.f;        t[1] = v.x;         t[2] = v.y;         t[3] = s01;
-      t[4] = v.z;        t[5] = v.x + v.z;   t[6] = v.y + v.z;   t[7] = s01 + v.z;
-      t[8] = v.w;        t[9] = v.x + v.w;   t[10] = v.y + v.w;  t[11] = s01 + v.w;
-      t[12] = s23;       t[13] = v.x + s23;  t[14] = v.y + s23;  t[15] = s01 + s23;
+      const float e[16] = {0.f,  v.x,       v.y,       s01,       v.z, v.x + v.z, v.y + v.z, s01 + v.z,
+                           v.w,  v.x + v.w, v.y + v.w, s01 + v.w, s23, v.x + s23, v.y + s23, s01 + s23};
+#pragma unroll
+      for (int n = 0; n < 16; ++n) t[n * kChunkWords] = e[n];
     }
     __syncthreads();
     for (int w = tid; w < n_word; w += kGemvThreads) {
       float sw = 0.f;
 #pragma unroll
-      for (int q = 0; q < 8; ++q) sw += T[(8 * w + q) * kLutStride + 15];
+      for (int q = 0; q < 8; ++q) sw += T[(q * 16 + 15) * kChunkWords + w];
       Sw[w] = sw;
     }
     __syncthreads();
@@ -69,14 +72,14 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_planes_kernel(const uint32_
         const float sw = Sw[w];
         acc0 = fmaf((float)coefs[(long)r0 * n_grp + G], sw, acc0);
         acc1 = fmaf((float)coefs[(long)r1 * n_grp + G], sw, acc1);
-        const float* tw = T + 8 * w * kLutStride;
+        const float* tw = T + w;
 #pragma unroll
         for (int i = 0; i < K; ++i) {
           float ma = 0.f, mb = 0.f;
 #pragma unroll
           for (int q = 0; q < 8; ++q) {
-            ma += tw[q * kLutStride + ((wa[i] >> (4 * q)) & 15u)];
-            mb += tw[q * kLutStride + ((wb[i] >> (4 * q)) & 15u)];
+            ma += tw[(q * 16 + ((wa[i] >> (4 * q)) & 15u)) * kChunkWords];
+            mb += tw[(q * 16 + ((wb[i] >> (4 * q)) & 15u)) * kChunkWords];
           }
           acc0 = fmaf((float)coefs[((long)(i + 1) * d_out + r0) * n_grp + G], ma, acc0);
           acc1 = fmaf((float)coefs[((long)(i + 1) * d_out + r1) * n_grp + G], mb, acc1);
