@@ -74,6 +74,17 @@ size_t bpdq_hessian_workspace_bytes(int n_tok, int d_in);
 int bpdq_hessian_accumulate(const float* Xc, int n_tok, int d_in, int ldx, float scale,
                             float* H, int symmetrize, void* ws, size_t ws_bytes, void* stream);
 
+/* The same update (Sec. 3.1, H = X X^T) computed on the bf16 matrix cores at fp32 accuracy:
+ * every value is cut exactly into three bf16 pieces and every product is the sum of the six
+ * piece products that matter, accumulated in fp32; the neglected terms are below 2^-24 of a
+ * product, i.e. below the rounding of the fp32 path.  Same arguments, requirements, workspace
+ * and return codes as bpdq_hessian_accumulate; H differs from it only by rounding (the results
+ * of the two calls are each bit-reproducible, but not bit-identical to one another).
+ * Assumes finite X with |x| < 2^127 (a value that rounds to infinity in bf16 yields NaN). */
+int bpdq_hessian_accumulate_bf16x3(const float* Xc, int n_tok, int d_in, int ldx, float scale,
+                                   float* H, int symmetrize, void* ws, size_t ws_bytes,
+                                   void* stream);
+
 /* ---- step 2: damping and U = chol(H^-1) (Sec. 3.1, "Quantization Error Compensation") ---
  * Reads the upper triangle of H.  Channels with H_ii == 0 are marked dead[i] = 1 and get
  * H_ii = 1.  Then lambda = damp * mean_i(H_ii), Ht = H + lambda I, and U is the upper

@@ -17,7 +17,7 @@ _lib = None
 
 EXPORTS = [
     "bpdq_version",
-    "bpdq_hessian_workspace_bytes", "bpdq_hessian_accumulate",
+    "bpdq_hessian_workspace_bytes", "bpdq_hessian_accumulate", "bpdq_hessian_accumulate_bf16x3",
     "bpdq_prepare_workspace_bytes", "bpdq_prepare",
     "bpdq_quantize_workspace_bytes", "bpdq_quantize_layer", "bpdq_quantize_layers",
     "bpdq_pack_planes", "bpdq_dequant", "bpdq_coefs_to_fp16", "bpdq_dequant_fp16",
@@ -53,6 +53,8 @@ def load():
     lib.bpdq_hessian_workspace_bytes.argtypes = [ci, ci]
     lib.bpdq_hessian_accumulate.restype = ci
     lib.bpdq_hessian_accumulate.argtypes = [vp, ci, ci, ci, cf, vp, ci, vp, sz, vp]
+    lib.bpdq_hessian_accumulate_bf16x3.restype = ci
+    lib.bpdq_hessian_accumulate_bf16x3.argtypes = [vp, ci, ci, ci, cf, vp, ci, vp, sz, vp]
     lib.bpdq_prepare_workspace_bytes.restype = sz
     lib.bpdq_prepare_workspace_bytes.argtypes = [ci]
     lib.bpdq_prepare.restype = ci
@@ -118,7 +120,13 @@ def bpdq_hessian_workspace_bytes(n_tok: int, d_in: int) -> int:
     return load().bpdq_hessian_workspace_bytes(n_tok, d_in)
 
 
-def bpdq_hessian_accumulate(Xc, H, scale=2.0, symmetrize=False, ws=None):
+def bpdq_hessian_accumulate_bf16x3(Xc, H, scale=2.0, symmetrize=False, ws=None):
+    """bpdq_hessian_accumulate on the bf16 matrix cores (three pieces per value, fp32 accuracy)."""
+    return bpdq_hessian_accumulate(Xc, H, scale, symmetrize, ws, _entry="bpdq_hessian_accumulate_bf16x3")
+
+
+def bpdq_hessian_accumulate(Xc, H, scale=2.0, symmetrize=False, ws=None,
+                            _entry="bpdq_hessian_accumulate"):
     """H += scale * Xc^T Xc (upper triangle; mirrored when symmetrize)."""
     lib = load()
     _dev(H, torch.float32, "H")
@@ -130,10 +138,10 @@ def bpdq_hessian_accumulate(Xc, H, scale=2.0, symmetrize=False, ws=None):
     need = lib.bpdq_hessian_workspace_bytes(n_tok, d_in)
     if ws is None:
         ws = _workspace(need, H.device)
-    rc = lib.bpdq_hessian_accumulate(_ptr(Xc), n_tok, d_in, Xc.stride(0) if n_tok > 1 else d_in,
-                                     scale, _ptr(H), int(bool(symmetrize)), _ptr(ws), ws.numel(),
-                                     _stream())
-    _check(rc, "bpdq_hessian_accumulate")
+    rc = getattr(lib, _entry)(_ptr(Xc), n_tok, d_in, Xc.stride(0) if n_tok > 1 else d_in,
+                              scale, _ptr(H), int(bool(symmetrize)), _ptr(ws), ws.numel(),
+                              _stream())
+    _check(rc, _entry)
     return H
 
 

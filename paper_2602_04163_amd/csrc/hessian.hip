@@ -8,6 +8,7 @@
 // Slice partials go to the workspace and are summed in a fixed order (no float atomics, so H is
 // bit-reproducible).
 #include "mfma_kmajor.h"
+#include "mfma_split_bf16.h"
 
 namespace bpdq {
 
@@ -44,10 +45,20 @@ static double hess_makespan(int n_full, double c_full, int n_short, double c_sho
   return t;
 }
 
-static HessPlan plan_hessian(int n_tok, int d_in) {
-  static HessPlan cache;
-  static int cache_n = -1, cache_d = -1;
-  if (n_tok == cache_n && d_in == cache_d) return cache;
+// The matrix cores truncate when they align the products of one instruction to the running sum,
+// so a sum of squares (the diagonal of H) drifts low in proportion to the number of instructions
+// chained into one accumulator: about -1.3e-6 for 11 k tokens on the fp32 path and -4.5e-6 for
+// 52 k tokens on the split path (16 products and 6 instructions per 16 tokens).  The split path
+// therefore ends every chain after kSplitChain tokens; the partial sums are added by ordinary
+// round-to-nearest fp32 additions, which do not drift.
+constexpr int kSplitChain = 8192;
+constexpr int kSplitMaxSlices = 64;
+
+// kind 0: fp32 MFMA kernel; kind 1: split-bf16 kernel (about 1.8 times the rate per token)
+static HessPlan plan_hessian(int n_tok, int d_in, int kind) {
+  static HessPlan cache[2];
+  static int cache_n[2] = {-1, -1}, cache_d[2] = {-1, -1};
+  if (n_tok == cache_n[kind] && d_in == cache_d[kind]) return cache[kind];
   HessPlan p;
   p.nb = bpdq_ceil_div(d_in, HessGemm::kTileM);
   p.n_diag = p.nb;
@@ -57,13 +68,17 @@ static HessPlan plan_hessian(int n_tok, int d_in) {
   p.direct = true;
   if (n_tok > 0 && p.n_off + p.n_diag < 4 * kNumCU) {
     // per-token MFMA time of one 256 x 256 tile, fixed cost per work-group, cost per partial tile
-    const double us_per_tok = 0.26, us_fixed = 8.0, us_per_partial = 0.131, diag_frac = 0.64;
-    const int s_max = n_tok / 256 < 64 ? (n_tok / 256 < 1 ? 1 : n_tok / 256) : 64;
+    const double us_per_tok = kind ? 0.14 : 0.26, us_fixed = 8.0, us_per_partial = 0.131;
+    const double diag_frac = 0.64;
+    const int s_max = n_tok / 256 < kSplitMaxSlices ? (n_tok / 256 < 1 ? 1 : n_tok / 256) : kSplitMaxSlices;
+    // the split kernel keeps every accumulation chain short (see kSplitChain)
+    int s_min = kind ? bpdq_ceil_div(n_tok, kSplitChain) : 1;
+    if (s_min > s_max) s_min = s_max;
     double best = 1e300;
-    for (int So = 1; So <= s_max; ++So) {
+    for (int So = s_min; So <= s_max; ++So) {
       for (int dd = -1; dd <= 1; ++dd) {
         int Sd = (int)(So * 0.625 + 0.5) + dd;
-        if (Sd < 1) Sd = 1;
+        if (Sd < s_min) Sd = s_min;
         if (Sd > s_max) Sd = s_max;
         const int ko = (int)bpdq_align_up((size_t)bpdq_ceil_div(n_tok, So), HessGemm::kStageK);
         const int kd = (int)bpdq_align_up((size_t)bpdq_ceil_div(n_tok, Sd), HessGemm::kStageK);
@@ -78,7 +93,7 @@ static HessPlan plan_hessian(int n_tok, int d_in) {
     }
     p.direct = (p.S_off == 1 && p.S_diag == 1);
   }
-  cache = p; cache_n = n_tok; cache_d = d_in;
+  cache[kind] = p; cache_n[kind] = n_tok; cache_d[kind] = d_in;
   return p;
 }
 
@@ -92,9 +107,12 @@ __device__ __forceinline__ void decode_off_tile(int tile, int nb, int& bi, int& 
   bj = bi + 1 + tile;
 }
 
-__global__ __launch_bounds__(HessGemm::kThreads) void hess_syrk_f32_kernel(
-    const float* __restrict__ X, int n_tok, int d, long ldx, float scale, float* __restrict__ H,
-    float* __restrict__ partial, HessPlan p) {
+// SPLIT false: fp32 matrix cores (v_mfma_f32_32x32x2_f32); true: three bf16 pieces per value and
+// six bf16 products per fp32 product (v_mfma_f32_32x32x16_bf16), same accumulator layout.
+template <bool SPLIT>
+__device__ __forceinline__ void hess_syrk_body(const float* __restrict__ X, int n_tok, int d,
+                                               long ldx, float scale, float* __restrict__ H,
+                                               float* __restrict__ partial, const HessPlan& p) {
   const int item = blockIdx.x;
   const int n_off_items = p.n_off * p.S_off;
   int bi, bj, k_begin, k_end;
@@ -111,30 +129,39 @@ __global__ __launch_bounds__(HessGemm::kThreads) void hess_syrk_f32_kernel(
   HessGemm::Acc acc;
   HessGemm::zero(acc);
   const int r0 = bi * HessGemm::kTileM, c0 = bj * HessGemm::kTileN;
+  // diagonal tile: only the 32 x 32 blocks on or above the diagonal are computed
+  if (bi == bj) {
+    if constexpr (SPLIT) SplitSyrk::run<true>(X, ldx, r0, c0, d, k_begin, k_end, acc);
+    else HessGemm::run<2>(X, ldx, r0, d, X, ldx, c0, d, k_begin, k_end, acc);
+  } else {
+    if constexpr (SPLIT) SplitSyrk::run<false>(X, ldx, r0, c0, d, k_begin, k_end, acc);
+    else HessGemm::run<0>(X, ldx, r0, d, X, ldx, c0, d, k_begin, k_end, acc);
+  }
   if (p.direct) {
     auto emit = [&](int row, int col, float v) {
       const int r = r0 + row, c = c0 + col;
       if (r < d && c < d) H[(long)r * d + c] += scale * v;
     };
-    if (bi == bj) {
-      HessGemm::run<2>(X, ldx, r0, d, X, ldx, c0, d, k_begin, k_end, acc);
-      HessGemm::for_each_diag(acc, emit);
-    } else {
-      HessGemm::run<0>(X, ldx, r0, d, X, ldx, c0, d, k_begin, k_end, acc);
-      HessGemm::for_each(acc, emit);
-    }
+    if (bi == bj) HessGemm::for_each_diag(acc, emit);
+    else HessGemm::for_each(acc, emit);
   } else {
     float* out = partial + (long)item * kTileFloats;
     auto emit = [&](int row, int col, float v) { out[row * HessGemm::kTileN + col] = v; };
-    if (bi == bj) {
-      // diagonal tile: only the 32 x 32 blocks on or above the diagonal are computed
-      HessGemm::run<2>(X, ldx, r0, d, X, ldx, c0, d, k_begin, k_end, acc);
-      HessGemm::for_each_diag(acc, emit);
-    } else {
-      HessGemm::run<0>(X, ldx, r0, d, X, ldx, c0, d, k_begin, k_end, acc);
-      HessGemm::for_each(acc, emit);
-    }
+    if (bi == bj) HessGemm::for_each_diag(acc, emit);
+    else HessGemm::for_each(acc, emit);
   }
+}
+
+__global__ __launch_bounds__(HessGemm::kThreads) void hess_syrk_f32_kernel(
+    const float* __restrict__ X, int n_tok, int d, long ldx, float scale, float* __restrict__ H,
+    float* __restrict__ partial, HessPlan p) {
+  hess_syrk_body<false>(X, n_tok, d, ldx, scale, H, partial, p);
+}
+
+__global__ __launch_bounds__(SplitSyrk::kThreads) void hess_syrk_bf16x3_kernel(
+    const float* __restrict__ X, int n_tok, int d, long ldx, float scale, float* __restrict__ H,
+    float* __restrict__ partial, HessPlan p) {
+  hess_syrk_body<true>(X, n_tok, d, ldx, scale, H, partial, p);
 }
 
 // H[tile] += scale * sum_s partial[s][tile], slices added in index order.  64 work-groups per
@@ -194,35 +221,57 @@ __global__ __launch_bounds__(256) void symmetrize_kernel(float* __restrict__ H, 
 
 using namespace bpdq;
 
-extern "C" size_t bpdq_hessian_workspace_bytes(int n_tok, int d_in) {
-  if (n_tok <= 0 || d_in <= 0) return 0;
-  return plan_hessian(n_tok, d_in).ws_bytes();
+// Tokens of the next launch.  The fp32 path takes a chunk whole.  The split path bounds the chain
+// length: a launch that adds straight into H (no slices) takes kSplitChain tokens, a sliced one
+// as many as its slices can cover; successive launches on one stream accumulate in order.
+static int hessian_launch_tokens(int kind, int n_left, int d_in) {
+  if (kind == 0) return n_left;
+  const long cover = (long)kSplitChain * kSplitMaxSlices;
+  int n = n_left > cover ? (int)cover : n_left;
+  if (n > kSplitChain && plan_hessian(n, d_in, kind).direct) n = kSplitChain;
+  return n;
 }
 
-extern "C" int bpdq_hessian_accumulate(const float* Xc, int n_tok, int d_in, int ldx, float scale,
-                                       float* H, int symmetrize, void* ws, size_t ws_bytes,
-                                       void* stream_) {
+// the first launch of a call is its largest
+static size_t hessian_ws_bytes(int kind, int n_tok, int d_in) {
+  return plan_hessian(hessian_launch_tokens(kind, n_tok, d_in), d_in, kind).ws_bytes();
+}
+
+static int hessian_accumulate(int kind, const float* Xc, int n_tok, int d_in, int ldx, float scale,
+                              float* H, int symmetrize, void* ws, size_t ws_bytes, void* stream_) {
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   if (n_tok < 0) return -2;
   if (d_in <= 0 || d_in % 4) return -3;
   if (ldx < d_in || ldx % 4) return -4;
   if (n_tok > 0 && (!Xc || (reinterpret_cast<uintptr_t>(Xc) & 15))) return -1;
   if (!H || (reinterpret_cast<uintptr_t>(H) & 15)) return -6;
-  if (n_tok > 0) {
-    const HessPlan p = plan_hessian(n_tok, d_in);
-    const size_t need = p.ws_bytes();
-    if (need > 0 && (!ws || (reinterpret_cast<uintptr_t>(ws) & 15))) return -8;
-    if (ws_bytes < need) return -9;
+  const size_t need = n_tok > 0 ? hessian_ws_bytes(kind, n_tok, d_in) : 0;
+  if (need > 0 && (!ws || (reinterpret_cast<uintptr_t>(ws) & 15))) return -8;
+  if (ws_bytes < need) return -9;
+  for (int done = 0; done < n_tok;) {
+    const int n_part = hessian_launch_tokens(kind, n_tok - done, d_in);
+    const HessPlan p = plan_hessian(n_part, d_in, kind);
+    const float* Xpart = Xc + (long)done * ldx;
+    done += n_part;
     static bool attr_set = false;
     if (!attr_set) {
       BPDQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(hess_syrk_f32_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)HessGemm::kLdsBytes));
+      BPDQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(hess_syrk_bf16x3_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)SplitSyrk::kLdsBytes));
       attr_set = true;
     }
-    hipLaunchKernelGGL(hess_syrk_f32_kernel, dim3(p.items()), dim3(HessGemm::kThreads),
-                       HessGemm::kLdsBytes, stream, Xc, n_tok, d_in, (long)ldx, scale, H,
-                       static_cast<float*>(ws), p);
+    if (kind == 0) {
+      hipLaunchKernelGGL(hess_syrk_f32_kernel, dim3(p.items()), dim3(HessGemm::kThreads),
+                         HessGemm::kLdsBytes, stream, Xpart, n_part, d_in, (long)ldx, scale, H,
+                         static_cast<float*>(ws), p);
+    } else {
+      hipLaunchKernelGGL(hess_syrk_bf16x3_kernel, dim3(p.items()), dim3(SplitSyrk::kThreads),
+                         SplitSyrk::kLdsBytes, stream, Xpart, n_part, d_in, (long)ldx, scale, H,
+                         static_cast<float*>(ws), p);
+    }
     BPDQ_LAUNCH_CHECK();
     if (!p.direct) {
       hipLaunchKernelGGL(hess_reduce_kernel, dim3((p.n_off + p.n_diag) * 64), dim3(256), 0, stream,
@@ -236,4 +285,23 @@ extern "C" int bpdq_hessian_accumulate(const float* Xc, int n_tok, int d_in, int
     BPDQ_LAUNCH_CHECK();
   }
   return 0;
+}
+
+extern "C" size_t bpdq_hessian_workspace_bytes(int n_tok, int d_in) {
+  if (n_tok <= 0 || d_in <= 0) return 0;
+  // one workspace serves either kernel
+  const size_t a = hessian_ws_bytes(0, n_tok, d_in), b = hessian_ws_bytes(1, n_tok, d_in);
+  return a > b ? a : b;
+}
+
+extern "C" int bpdq_hessian_accumulate(const float* Xc, int n_tok, int d_in, int ldx, float scale,
+                                       float* H, int symmetrize, void* ws, size_t ws_bytes,
+                                       void* stream) {
+  return hessian_accumulate(0, Xc, n_tok, d_in, ldx, scale, H, symmetrize, ws, ws_bytes, stream);
+}
+
+extern "C" int bpdq_hessian_accumulate_bf16x3(const float* Xc, int n_tok, int d_in, int ldx,
+                                              float scale, float* H, int symmetrize, void* ws,
+                                              size_t ws_bytes, void* stream) {
+  return hessian_accumulate(1, Xc, n_tok, d_in, ldx, scale, H, symmetrize, ws, ws_bytes, stream);
 }

@@ -39,7 +39,7 @@ def _log(msg):
     print(f"[{time.strftime('%H:%M:%S')}] {msg}", flush=True)
 
 
-def _end_to_end(dev, wl, tokens_per_call=0):
+def _end_to_end(dev, wl, tokens_per_call=0, hess=None):
     """Whole pass on both sides from the same seeded inputs; returns the parity numbers."""
     d_in = wl.d_in
     W = wk.make_weight(wl, device=dev)
@@ -50,9 +50,10 @@ def _end_to_end(dev, wl, tokens_per_call=0):
     # ---- GPU: every step inside the library
     H = torch.zeros((d_in, d_in), device=dev)
     per = tokens_per_call or wl.n_tok
+    hess = hess or bq.bpdq_hessian_accumulate
     for a in range(0, wl.n_tok, per):
         b = min(a + per, wl.n_tok)
-        bq.bpdq_hessian_accumulate(X[a:b], H, symmetrize=(b == wl.n_tok))
+        hess(X[a:b], H, symmetrize=(b == wl.n_tok))
     U, dead, info = bq.bpdq_prepare(H, wl.damp)
     p = bq.make_params(wl.bits, wl.group, wl.block, wl.refine_iters, wl.alpha)
     out = bq.bpdq_quantize_layer(W, U, dead, p)
@@ -105,10 +106,13 @@ def _end_to_end(dev, wl, tokens_per_call=0):
     return dict(h_err=h_err, plane_frac=plane_frac, obj_gpu=o_g, obj_oracle=o_r)
 
 
-def test_benchmark_workload_full_size(dev):
+@pytest.mark.parametrize("hess", ["bf16x3", "f32"])
+def test_benchmark_workload_full_size(dev, hess):
     """configs[1]: 3584 x 3584, 262144 tokens, 2-bit, g = B = 128, 5 iterations; one Hessian
-    call over all tokens, exactly as bench.py launches it."""
-    _end_to_end(dev, wk.WORKLOADS["cfg2_qwen7b_attn"])
+    call over all tokens, exactly as bench.py launches it (bench.py times the bf16x3 entry
+    point; the fp32 one is the alternative)."""
+    fn = {"f32": bq.bpdq_hessian_accumulate, "bf16x3": bq.bpdq_hessian_accumulate_bf16x3}[hess]
+    _end_to_end(dev, wk.WORKLOADS["cfg2_qwen7b_attn"], hess=fn)
 
 
 def test_benchmark_workload_chunked_hessian(dev):
@@ -116,6 +120,7 @@ def test_benchmark_workload_chunked_hessian(dev):
     oracle stays short)."""
     wl = wk.WORKLOADS["cfg2_qwen7b_attn"].scaled(n_tok=16384)
     _end_to_end(dev, wl, tokens_per_call=4096)
+    _end_to_end(dev, wl, tokens_per_call=4096, hess=bq.bpdq_hessian_accumulate_bf16x3)
 
 
 SCALED = {

@@ -37,15 +37,25 @@ def _problem(name, d_out, d_in, n_tok, **kw):
 
 
 # ------------------------------------------------------------------ step 1: Hessian
-@pytest.mark.parametrize("n_tok,d_in", [(100, 96), (512, 256), (1000, 640), (5000, 776), (37, 4)])
-def test_hessian_matches_oracle(dev, n_tok, d_in):
-    print(f"hessian n_tok={n_tok} d_in={d_in}", flush=True)
+# both entry points: the fp32 matrix-core kernel and the three-piece bf16 one
+HESSIAN_CALLS = {"f32": bq.bpdq_hessian_accumulate, "bf16x3": bq.bpdq_hessian_accumulate_bf16x3}
+
+
+@pytest.fixture(params=["f32", "bf16x3"])
+def hess(request):
+    return HESSIAN_CALLS[request.param]
+
+
+@pytest.mark.parametrize("n_tok,d_in", [(100, 96), (512, 256), (1000, 640), (5000, 776), (37, 4), (16, 260),
+                                        (17, 516), (20000, 264)])
+def test_hessian_matches_oracle(dev, hess, n_tok, d_in):
+    print(f"hessian {hess.__name__} n_tok={n_tok} d_in={d_in}", flush=True)
     g = torch.Generator().manual_seed(n_tok * 1000 + d_in)
     X = torch.randn((n_tok, d_in), generator=g) * torch.exp(torch.randn(d_in, generator=g))
     Href = np.zeros((d_in, d_in))
     orc.hessian_accumulate(X.numpy(), Href)
     H = torch.zeros((d_in, d_in), device=dev)
-    bq.bpdq_hessian_accumulate(X.to(dev), H, symmetrize=True)
+    hess(X.to(dev), H, symmetrize=True)
     Hg = H.cpu().numpy().astype(np.float64)
     assert _relfro(Hg, Href) < H_TOL
     assert np.array_equal(Hg, Hg.T)
@@ -54,8 +64,8 @@ def test_hessian_matches_oracle(dev, n_tok, d_in):
     assert np.max(np.abs(Hg - Href) / scale) < 2e-5
 
 
-def test_hessian_chunks_strided_and_deterministic(dev):
-    print("hessian chunked", flush=True)
+def test_hessian_chunks_strided_and_deterministic(dev, hess):
+    print(f"hessian chunked {hess.__name__}", flush=True)
     n_tok, d_in = 3000, 520
     g = torch.Generator().manual_seed(7)
     Xfull = torch.randn((n_tok, d_in + 8), generator=g)
@@ -67,14 +77,45 @@ def test_hessian_chunks_strided_and_deterministic(dev):
         H = torch.zeros((d_in, d_in), device=dev)
         edges = [0, 1000, 1016, 2500, 3000]
         for a, b in zip(edges[:-1], edges[1:]):
-            bq.bpdq_hessian_accumulate(Xd[a:b], H, symmetrize=(b == n_tok))
+            hess(Xd[a:b], H, symmetrize=(b == n_tok))
         outs.append(H.cpu().numpy())
     assert np.array_equal(outs[0], outs[1])       # no float atomics: bit-reproducible
     assert _relfro(outs[0].astype(np.float64), Href) < H_TOL
     # empty chunk is a no-op
     H0 = torch.ones((d_in, d_in), device=dev)
-    bq.bpdq_hessian_accumulate(Xd[:0], H0)
+    hess(Xd[:0], H0)
     assert bool((H0 == 1).all())
+
+
+def test_hessian_bf16x3_exact_on_short_values(dev):
+    """Values with at most 8 significant bits are their own first piece, and small integers make
+    every partial sum exact in fp32: both kernels must then return the exact H, bit for bit."""
+    print("hessian exact integers", flush=True)
+    n_tok, d_in = 3000, 520
+    g = torch.Generator().manual_seed(11)
+    X = torch.randint(-15, 16, (n_tok, d_in), generator=g).float()
+    Href = 2.0 * (X.double().T @ X.double())
+    for name, fn in HESSIAN_CALLS.items():
+        H = torch.zeros((d_in, d_in), device=dev)
+        fn(X.to(dev), H, symmetrize=True)
+        assert torch.equal(H.cpu().double(), Href), name
+
+
+def test_hessian_bf16x3_long_accumulation(dev):
+    """More tokens than one accumulation chain of the split kernel holds (8192), on a ragged
+    two-tile width: slices and their fixed-order sum, checked entry by entry."""
+    print("hessian bf16x3 long", flush=True)
+    n_tok, d_in = 40000, 300
+    g = torch.Generator().manual_seed(12)
+    X = torch.randn((n_tok, d_in), generator=g) * torch.exp(1.5 * torch.randn(d_in, generator=g))
+    Href = np.zeros((d_in, d_in))
+    orc.hessian_accumulate(X.numpy(), Href)
+    H = torch.zeros((d_in, d_in), device=dev)
+    bq.bpdq_hessian_accumulate_bf16x3(X.to(dev), H, symmetrize=True)
+    Hg = H.cpu().numpy().astype(np.float64)
+    assert _relfro(Hg, Href) < H_TOL
+    scale = np.sqrt(np.outer(np.diag(Href), np.diag(Href)))
+    assert np.max(np.abs(Hg - Href) / scale) < 2e-5
 
 
 # ------------------------------------------------------------------ step 2: prepare
