@@ -18,6 +18,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_MFMA_F32_TFLOPS = 157.3    # MI355X dense fp32 matrix peak
+PEAK_MFMA_BF16_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
+SPLIT_PRODUCTS = 6              # bf16 products the split kernel issues per fp32 product
 
 
 def parse():
@@ -28,6 +30,8 @@ def parse():
     ap.add_argument("--workload", default="cfg2_qwen7b_attn")
     ap.add_argument("--tokens-per-call", type=int, default=0,
                     help="tokens per bpdq_hessian_accumulate call (0 = all tokens in one call)")
+    ap.add_argument("--hessian", choices=["bf16x3", "f32"], default="bf16x3",
+                    help="Hessian kernel: three-piece bf16 split (default) or fp32 matrix cores")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB -> 1 GiB elementwise kernel (scale for HBM counters)")
@@ -111,6 +115,9 @@ def main():
     phases = [s for s in args.phases_only.split(",") if s] or ["hessian", "prepare", "quantize"]
     ev = {k: [] for k in ("hessian", "prepare", "quantize")}
 
+    hessian_call = (bq.bpdq_hessian_accumulate_bf16x3 if args.hessian == "bf16x3"
+                    else bq.bpdq_hessian_accumulate)
+
     def step(record):
         nonlocal out
         marks = [torch.cuda.Event(enable_timing=True) for _ in range(4)] if record else None
@@ -119,7 +126,7 @@ def main():
         if "hessian" in phases:
             H.zero_()
             for a, b in calls:
-                bq.bpdq_hessian_accumulate(X[a:b], H, scale=2.0, symmetrize=False, ws=ws_h)
+                hessian_call(X[a:b], H, scale=2.0, symmetrize=False, ws=ws_h)
         if record:
             marks[1].record()
         dead = None
@@ -158,15 +165,25 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     phase_ms = {k: sum(a.elapsed_time(b) for a, b in v) / max(len(v), 1) for k, v in ev.items()}
 
-    # ---- roofline of the dominant kernel: the fp32-MFMA Hessian SYRK ---------------------
+    # ---- roofline of the dominant kernel: the Hessian SYRK -------------------------------
     # algorithmic flops: the symmetric half, d(d+1) multiply-adds' worth per token
     flops_per_launch = float(d_in) * (d_in + 1) * (n_tok / len(calls))
     launch_ms = phase_ms["hessian"] / len(calls)
     achieved = flops_per_launch / (launch_ms * 1e-3) / 1e12 if launch_ms > 0 else 0.0
     traffic = None
-    tp = os.path.join(ROOT, "profiles", f"hess_syrk_{args.workload}_traffic.json")   # from rocprofv3 --pmc runs
+    kernel = "hess_syrk_bf16x3_kernel" if args.hessian == "bf16x3" else "hess_syrk_f32_kernel"
+    tp = os.path.join(ROOT, "profiles", f"{kernel[:-7]}_{args.workload}_traffic.json")   # from rocprofv3 --pmc runs
     if os.path.exists(tp) and len(calls) == 1:
         traffic = json.load(open(tp)).get("hbm_bytes_per_launch")
+    if args.hessian == "bf16x3":
+        # `achieved` counts the fp32 products of the update; the kernel issues six bf16 products for
+        # each, so its ceiling on the bf16 pipe is a sixth of that pipe's peak
+        peak = PEAK_MFMA_BF16_TFLOPS / SPLIT_PRODUCTS
+        roof_extra = {"issued": achieved * SPLIT_PRODUCTS, "issued_peak": PEAK_MFMA_BF16_TFLOPS,
+                      "vs_fp32_mfma_peak": achieved / PEAK_MFMA_F32_TFLOPS,
+                      "note": "fp32-accurate product as six bf16 MFMA products; peak = bf16 dense peak / 6"}
+    else:
+        peak, roof_extra = PEAK_MFMA_F32_TFLOPS, {}
     res = {
         "metric": "Mparams quantized/s per layer (full pass: Hessian + prepare + sweep)",
         "value": wl.params / (ms_per_step * 1e-3) / 1e6,
@@ -174,16 +191,18 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "f32 (Hessian products as 3 x bf16 pieces, fp32 accumulate)" if args.hessian == "bf16x3" else "f32",
+        "data": "synthetic",
         "config": {"workload": wl.name, "d_out": d_out, "d_in": d_in, "tokens": n_tok,
                    "bits": wl.bits, "group": wl.group, "block": wl.block,
-                   "refine_iters": wl.refine_iters, "hessian_calls_per_step": len(calls)},
+                   "refine_iters": wl.refine_iters, "hessian_calls_per_step": len(calls),
+                   "hessian_kernel": args.hessian},
         "phase_ms": {k: round(v, 4) for k, v in phase_ms.items()},
         "quantize_only_mparams_per_s": (wl.params / (phase_ms["quantize"] * 1e-3) / 1e6
                                         if phase_ms["quantize"] > 0 else None),
-        "roofline": {"kernel": "hess_syrk_f32_kernel", "bound": "mfma", "achieved": achieved,
-                     "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_MFMA_F32_TFLOPS, "traffic": traffic},
+        "roofline": {"kernel": kernel, "bound": "mfma", "achieved": achieved,
+                     "peak": peak, "unit": "TFLOP/s",
+                     "frac": achieved / peak, "traffic": traffic, **roof_extra},
     }
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(wl, W.cpu(), scales.cpu())

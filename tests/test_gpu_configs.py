@@ -157,12 +157,14 @@ def test_other_workloads_full_shape(dev, name):
 
 
 @pytest.mark.skipif(not FULL, reason="set BPDQ_FULL_CONFIGS=1")
+@pytest.mark.parametrize("hess", ["f32", "bf16x3"])
 @pytest.mark.parametrize("name", ["cfg4_qwen72b_attn", "cfg5_qwen72b_down"])
-def test_full_token_hessian_sampled(dev, name):
+def test_full_token_hessian_sampled(dev, name, hess):
     """All 262144 tokens at full width, streamed in 4096-token calls; H is checked on a
     sampled 96 x 96 sub-matrix, which depends only on the 96 sampled input channels."""
     wl = wk.WORKLOADS[name]
     d_in = wl.d_in
+    accumulate = {"f32": bq.bpdq_hessian_accumulate, "bf16x3": bq.bpdq_hessian_accumulate_bf16x3}[hess]
     scales = wk.channel_scales(wl, device=dev)
     idx = torch.randperm(d_in, generator=torch.Generator().manual_seed(5))[:96].sort().values
     H = torch.zeros((d_in, d_in), device=dev)
@@ -170,12 +172,12 @@ def test_full_token_hessian_sampled(dev, name):
     buf = torch.empty((wl.chunk, d_in), device=dev)
     for c in range(wk.n_chunks(wl)):
         Xc = wk.make_activation_chunk(wl, c, scales, device=dev, out=buf)
-        bq.bpdq_hessian_accumulate(Xc, H, symmetrize=(c == wk.n_chunks(wl) - 1))
+        accumulate(Xc, H, symmetrize=(c == wk.n_chunks(wl) - 1))
         orc.hessian_accumulate(Xc[:, idx.to(dev)].cpu().numpy(), Hsub)
         if c % 16 == 0:
             _log(f"{name}: chunk {c}")
     torch.cuda.synchronize()
     Hg = H[idx.to(dev)][:, idx.to(dev)].cpu().numpy().astype(np.float64)
     err = float(np.linalg.norm(Hg - Hsub) / np.linalg.norm(Hsub))
-    _log(f"{name}: full-token H, sampled 96x96 relFro {err:.2e}")
+    _log(f"{name}: full-token H ({hess}), sampled 96x96 relFro {err:.2e}")
     assert err < H_TOL
