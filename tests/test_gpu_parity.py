@@ -118,6 +118,33 @@ def test_hessian_bf16x3_long_accumulation(dev):
     assert np.max(np.abs(Hg - Href) / scale) < 2e-5
 
 
+def test_hessian_bf16x3_host_split_launches(dev):
+    """The split kernel bounds its accumulation chains at 8192 tokens.  Two host-side cases:
+    a layer wide enough to add straight into H (>= 1024 tiles) is cut into 8192-token launches,
+    and a call with more tokens than 64 slices of 8192 cover is cut as well."""
+    print("hessian bf16x3 wide layer, 9000 tokens", flush=True)
+    d_in, n_tok = 11520, 9000
+    g = torch.Generator(device=dev).manual_seed(13)
+    X = torch.randn((n_tok, d_in), generator=g, device=dev)
+    idx = torch.randperm(d_in, generator=torch.Generator().manual_seed(5))[:96].sort().values.to(dev)
+    H = torch.zeros((d_in, d_in), device=dev)
+    bq.bpdq_hessian_accumulate_bf16x3(X, H, symmetrize=True)
+    Hsub = np.zeros((96, 96))
+    orc.hessian_accumulate(X[:, idx].cpu().numpy(), Hsub)
+    Hg = H[idx][:, idx].cpu().numpy().astype(np.float64)
+    assert _relfro(Hg, Hsub) < H_TOL
+    assert torch.equal(H, H.T)
+    del X, H
+    print("hessian bf16x3 530000 tokens", flush=True)
+    d_in, n_tok = 8, 530000
+    X = torch.randn((n_tok, d_in), generator=g, device=dev) * 3.0
+    H = torch.zeros((d_in, d_in), device=dev)
+    bq.bpdq_hessian_accumulate_bf16x3(X, H, symmetrize=True)
+    Href = np.zeros((d_in, d_in))
+    orc.hessian_accumulate(X.cpu().numpy(), Href)
+    assert _relfro(H.cpu().numpy().astype(np.float64), Href) < H_TOL
+
+
 # ------------------------------------------------------------------ step 2: prepare
 @pytest.mark.parametrize("d_in,sigma", [(96, 1.0), (200, 1.0), (640, 1.5), (1288, 1.0)])
 def test_prepare_matches_oracle(dev, d_in, sigma):
