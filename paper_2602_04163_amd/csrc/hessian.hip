@@ -107,14 +107,37 @@ __device__ __forceinline__ void decode_off_tile(int tile, int nb, int& bi, int& 
   bj = bi + 1 + tile;
 }
 
+// Work-group -> work item.  Work-groups are handed to the 8 XCDs round-robin (work-group w runs
+// on XCD w % 8), each XCD has its own L2, and items are numbered slice-major (item = slice *
+// tiles + tile).  Taken in that order every XCD would work on all token slices at once and each
+// L2 would stream the whole of X: 8 x the traffic.  Instead XCD x takes the slices congruent to
+// x modulo 8, tile after tile: the work-groups running on an XCD at one time walk the same
+// tokens in step, its L2 serves every 256-channel block of a stage to all of them from one
+// fetch, and each token is fetched by one XCD only.  Slices beyond the last multiple of 8 keep
+// the plain order.  The map is a bijection on the items, so partials and reduction are unchanged.
+__device__ __forceinline__ int xcd_item(int w, int n_off_items, const HessPlan& p) {
+  int base = 0, tiles = p.n_off, slices = p.S_off;
+  if (w >= n_off_items) {
+    base = n_off_items;
+    tiles = p.n_diag;
+    slices = p.S_diag;
+  }
+  const int j = w - base;
+  const int grouped = tiles * (slices / kNumXCD) * kNumXCD;   // items of the slices that are remapped
+  if (j >= grouped) return w;
+  // j % 8 names the XCD up to a fixed rotation (base need not be a multiple of 8)
+  const int y = j % kNumXCD, q = j / kNumXCD;
+  return base + ((q / tiles) * kNumXCD + y) * tiles + q % tiles;
+}
+
 // SPLIT false: fp32 matrix cores (v_mfma_f32_32x32x2_f32); true: three bf16 pieces per value and
 // six bf16 products per fp32 product (v_mfma_f32_32x32x16_bf16), same accumulator layout.
 template <bool SPLIT>
 __device__ __forceinline__ void hess_syrk_body(const float* __restrict__ X, int n_tok, int d,
                                                long ldx, float scale, float* __restrict__ H,
                                                float* __restrict__ partial, const HessPlan& p) {
-  const int item = blockIdx.x;
   const int n_off_items = p.n_off * p.S_off;
+  const int item = xcd_item(blockIdx.x, n_off_items, p);
   int bi, bj, k_begin, k_end;
   if (item < n_off_items) {
     decode_off_tile(item % p.n_off, p.nb, bi, bj);
