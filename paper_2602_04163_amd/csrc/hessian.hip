@@ -1,7 +1,9 @@
 // Step 1 of the pass: calibration Hessian H += scale * Xc^T Xc (paper Sec. 3.1, H = X X^T).
 //
-// A symmetric rank-k update on the fp32 matrix cores.  Only the upper triangle of 256 x 256
-// tiles is computed, and of a diagonal tile only the 32 x 32 blocks on or above the diagonal.
+// A symmetric rank-k update on the matrix cores, in two kernels that share everything but the
+// tile product: fp32 MFMAs (bpdq_hessian_accumulate), or bf16 MFMAs on three exact bf16 pieces
+// of every value (bpdq_hessian_accumulate_bf16x3; mfma_split_bf16.h).  Only the upper triangle
+// of 256 x 256 tiles is computed, and of a diagonal tile only the 32 x 32 blocks on or above the diagonal.
 // The token axis is cut into deterministic slices so that the work-groups fill the 256 compute
 // units in whole rounds: off-diagonal tiles into S_off slices, diagonal tiles (5/8 of the work
 // per token) into fewer, longer slices S_diag, so that every work-group costs about the same.
