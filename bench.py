@@ -115,8 +115,8 @@ def main():
     phases = [s for s in args.phases_only.split(",") if s] or ["hessian", "prepare", "quantize"]
     ev = {k: [] for k in ("hessian", "prepare", "quantize")}
 
-    hessian_call = (bq.bpdq_hessian_accumulate_bf16x3 if args.hessian == "bf16x3"
-                    else bq.bpdq_hessian_accumulate)
+    hessian_call = (bq.bpdq_hessian_accumulate if args.hessian == "bf16x3"
+                    else bq.bpdq_hessian_accumulate_f32)
 
     def step(record):
         nonlocal out

@@ -69,21 +69,25 @@ int bpdq_version(void);
  *   scale : 2 reproduces the customary H = 2 X X^T; any positive factor gives the same
  *        planes and coefficients.
  *   ws : split-K partial sums; bpdq_hessian_workspace_bytes(n_tok, d_in) bytes (may be 0).
- * Requirements: d_in % 4 == 0, ldx % 4 == 0, Xc and H 16-byte aligned, n_tok >= 0. */
+ * Requirements: d_in % 4 == 0, ldx % 4 == 0, Xc and H 16-byte aligned, n_tok >= 0.
+ * Returns 0, or a negative code naming the offending argument (-1 Xc, -2 n_tok, -3 d_in,
+ * -4 ldx, -6 H, -8 ws, -9 ws_bytes); nothing is launched then.
+ *
+ * bpdq_hessian_accumulate runs on the bf16 matrix cores at fp32 accuracy: every value is cut
+ * exactly into three bf16 pieces and every product is the sum of the six piece products that
+ * matter, accumulated in fp32; the neglected terms are below 2^-24 of a product, i.e. below
+ * the rounding of an fp32 product.  It assumes finite X with |x| < 2^127 (a value that rounds
+ * to infinity in bf16 yields NaN).
+ * bpdq_hessian_accumulate_f32 is the same update on the fp32 matrix cores (about 1.5 times
+ * slower): same arguments, requirements, workspace and return codes.  The two results differ
+ * only by rounding; each is bit-reproducible from call to call, they are not bit-identical to
+ * one another. */
 size_t bpdq_hessian_workspace_bytes(int n_tok, int d_in);
 int bpdq_hessian_accumulate(const float* Xc, int n_tok, int d_in, int ldx, float scale,
                             float* H, int symmetrize, void* ws, size_t ws_bytes, void* stream);
-
-/* The same update (Sec. 3.1, H = X X^T) computed on the bf16 matrix cores at fp32 accuracy:
- * every value is cut exactly into three bf16 pieces and every product is the sum of the six
- * piece products that matter, accumulated in fp32; the neglected terms are below 2^-24 of a
- * product, i.e. below the rounding of the fp32 path.  Same arguments, requirements, workspace
- * and return codes as bpdq_hessian_accumulate; H differs from it only by rounding (the results
- * of the two calls are each bit-reproducible, but not bit-identical to one another).
- * Assumes finite X with |x| < 2^127 (a value that rounds to infinity in bf16 yields NaN). */
-int bpdq_hessian_accumulate_bf16x3(const float* Xc, int n_tok, int d_in, int ldx, float scale,
-                                   float* H, int symmetrize, void* ws, size_t ws_bytes,
-                                   void* stream);
+int bpdq_hessian_accumulate_f32(const float* Xc, int n_tok, int d_in, int ldx, float scale,
+                                float* H, int symmetrize, void* ws, size_t ws_bytes,
+                                void* stream);
 
 /* ---- step 2: damping and U = chol(H^-1) (Sec. 3.1, "Quantization Error Compensation") ---
  * Reads the upper triangle of H.  Channels with H_ii == 0 are marked dead[i] = 1 and get

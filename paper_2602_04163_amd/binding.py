@@ -17,7 +17,7 @@ _lib = None
 
 EXPORTS = [
     "bpdq_version",
-    "bpdq_hessian_workspace_bytes", "bpdq_hessian_accumulate", "bpdq_hessian_accumulate_bf16x3",
+    "bpdq_hessian_workspace_bytes", "bpdq_hessian_accumulate_f32", "bpdq_hessian_accumulate",
     "bpdq_prepare_workspace_bytes", "bpdq_prepare",
     "bpdq_quantize_workspace_bytes", "bpdq_quantize_layer", "bpdq_quantize_layers",
     "bpdq_pack_planes", "bpdq_dequant", "bpdq_coefs_to_fp16", "bpdq_dequant_fp16",
@@ -51,10 +51,10 @@ def load():
     lib.bpdq_version.argtypes = []
     lib.bpdq_hessian_workspace_bytes.restype = sz
     lib.bpdq_hessian_workspace_bytes.argtypes = [ci, ci]
+    lib.bpdq_hessian_accumulate_f32.restype = ci
+    lib.bpdq_hessian_accumulate_f32.argtypes = [vp, ci, ci, ci, cf, vp, ci, vp, sz, vp]
     lib.bpdq_hessian_accumulate.restype = ci
     lib.bpdq_hessian_accumulate.argtypes = [vp, ci, ci, ci, cf, vp, ci, vp, sz, vp]
-    lib.bpdq_hessian_accumulate_bf16x3.restype = ci
-    lib.bpdq_hessian_accumulate_bf16x3.argtypes = [vp, ci, ci, ci, cf, vp, ci, vp, sz, vp]
     lib.bpdq_prepare_workspace_bytes.restype = sz
     lib.bpdq_prepare_workspace_bytes.argtypes = [ci]
     lib.bpdq_prepare.restype = ci
@@ -120,14 +120,9 @@ def bpdq_hessian_workspace_bytes(n_tok: int, d_in: int) -> int:
     return load().bpdq_hessian_workspace_bytes(n_tok, d_in)
 
 
-def bpdq_hessian_accumulate_bf16x3(Xc, H, scale=2.0, symmetrize=False, ws=None):
-    """bpdq_hessian_accumulate on the bf16 matrix cores (three pieces per value, fp32 accuracy)."""
-    return bpdq_hessian_accumulate(Xc, H, scale, symmetrize, ws, _entry="bpdq_hessian_accumulate_bf16x3")
-
-
-def bpdq_hessian_accumulate(Xc, H, scale=2.0, symmetrize=False, ws=None,
-                            _entry="bpdq_hessian_accumulate"):
-    """H += scale * Xc^T Xc (upper triangle; mirrored when symmetrize)."""
+def bpdq_hessian_accumulate(Xc, H, scale=2.0, symmetrize=False, ws=None, _entry="bpdq_hessian_accumulate"):
+    """H += scale * Xc^T Xc (upper triangle; mirrored when symmetrize), on the bf16 matrix cores
+    with three exact bf16 pieces per value (fp32 accuracy)."""
     lib = load()
     _dev(H, torch.float32, "H")
     if not (Xc.is_cuda and Xc.dtype == torch.float32 and Xc.dim() == 2 and Xc.stride(1) == 1):
@@ -143,6 +138,11 @@ def bpdq_hessian_accumulate(Xc, H, scale=2.0, symmetrize=False, ws=None,
                               _stream())
     _check(rc, _entry)
     return H
+
+
+def bpdq_hessian_accumulate_f32(Xc, H, scale=2.0, symmetrize=False, ws=None):
+    """bpdq_hessian_accumulate on the fp32 matrix cores."""
+    return bpdq_hessian_accumulate(Xc, H, scale, symmetrize, ws, _entry="bpdq_hessian_accumulate_f32")
 
 
 def bpdq_prepare_workspace_bytes(d_in: int) -> int:

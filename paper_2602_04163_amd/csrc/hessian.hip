@@ -1,8 +1,8 @@
 // Step 1 of the pass: calibration Hessian H += scale * Xc^T Xc (paper Sec. 3.1, H = X X^T).
 //
 // A symmetric rank-k update on the matrix cores, in two kernels that share everything but the
-// tile product: fp32 MFMAs (bpdq_hessian_accumulate), or bf16 MFMAs on three exact bf16 pieces
-// of every value (bpdq_hessian_accumulate_bf16x3; mfma_split_bf16.h).  Only the upper triangle
+// tile product: fp32 MFMAs (bpdq_hessian_accumulate_f32), or bf16 MFMAs on three exact bf16 pieces
+// of every value (bpdq_hessian_accumulate; mfma_split_bf16.h).  Only the upper triangle
 // of 256 x 256 tiles is computed, and of a diagonal tile only the 32 x 32 blocks on or above the diagonal.
 // The token axis is cut into deterministic slices so that the work-groups fill the 256 compute
 // units in whole rounds: off-diagonal tiles into S_off slices, diagonal tiles (5/8 of the work
@@ -319,13 +319,13 @@ extern "C" size_t bpdq_hessian_workspace_bytes(int n_tok, int d_in) {
   return a > b ? a : b;
 }
 
-extern "C" int bpdq_hessian_accumulate(const float* Xc, int n_tok, int d_in, int ldx, float scale,
+extern "C" int bpdq_hessian_accumulate_f32(const float* Xc, int n_tok, int d_in, int ldx, float scale,
                                        float* H, int symmetrize, void* ws, size_t ws_bytes,
                                        void* stream) {
   return hessian_accumulate(0, Xc, n_tok, d_in, ldx, scale, H, symmetrize, ws, ws_bytes, stream);
 }
 
-extern "C" int bpdq_hessian_accumulate_bf16x3(const float* Xc, int n_tok, int d_in, int ldx,
+extern "C" int bpdq_hessian_accumulate(const float* Xc, int n_tok, int d_in, int ldx,
                                               float scale, float* H, int symmetrize, void* ws,
                                               size_t ws_bytes, void* stream) {
   return hessian_accumulate(1, Xc, n_tok, d_in, ldx, scale, H, symmetrize, ws, ws_bytes, stream);

@@ -109,9 +109,9 @@ def _end_to_end(dev, wl, tokens_per_call=0, hess=None):
 @pytest.mark.parametrize("hess", ["bf16x3", "f32"])
 def test_benchmark_workload_full_size(dev, hess):
     """configs[1]: 3584 x 3584, 262144 tokens, 2-bit, g = B = 128, 5 iterations; one Hessian
-    call over all tokens, exactly as bench.py launches it (bench.py times the bf16x3 entry
-    point; the fp32 one is the alternative)."""
-    fn = {"f32": bq.bpdq_hessian_accumulate, "bf16x3": bq.bpdq_hessian_accumulate_bf16x3}[hess]
+    call over all tokens, exactly as bench.py launches it (bench.py times bpdq_hessian_accumulate,
+    the bf16x3 kernel; bpdq_hessian_accumulate_f32 is the alternative)."""
+    fn = {"f32": bq.bpdq_hessian_accumulate_f32, "bf16x3": bq.bpdq_hessian_accumulate}[hess]
     _end_to_end(dev, wk.WORKLOADS["cfg2_qwen7b_attn"], hess=fn)
 
 
@@ -120,7 +120,7 @@ def test_benchmark_workload_chunked_hessian(dev):
     oracle stays short)."""
     wl = wk.WORKLOADS["cfg2_qwen7b_attn"].scaled(n_tok=16384)
     _end_to_end(dev, wl, tokens_per_call=4096)
-    _end_to_end(dev, wl, tokens_per_call=4096, hess=bq.bpdq_hessian_accumulate_bf16x3)
+    _end_to_end(dev, wl, tokens_per_call=4096, hess=bq.bpdq_hessian_accumulate_f32)
 
 
 SCALED = {
@@ -164,7 +164,7 @@ def test_full_token_hessian_sampled(dev, name, hess):
     sampled 96 x 96 sub-matrix, which depends only on the 96 sampled input channels."""
     wl = wk.WORKLOADS[name]
     d_in = wl.d_in
-    accumulate = {"f32": bq.bpdq_hessian_accumulate, "bf16x3": bq.bpdq_hessian_accumulate_bf16x3}[hess]
+    accumulate = {"f32": bq.bpdq_hessian_accumulate_f32, "bf16x3": bq.bpdq_hessian_accumulate}[hess]
     scales = wk.channel_scales(wl, device=dev)
     idx = torch.randperm(d_in, generator=torch.Generator().manual_seed(5))[:96].sort().values
     H = torch.zeros((d_in, d_in), device=dev)

@@ -38,7 +38,7 @@ def _problem(name, d_out, d_in, n_tok, **kw):
 
 # ------------------------------------------------------------------ step 1: Hessian
 # both entry points: the fp32 matrix-core kernel and the three-piece bf16 one
-HESSIAN_CALLS = {"f32": bq.bpdq_hessian_accumulate, "bf16x3": bq.bpdq_hessian_accumulate_bf16x3}
+HESSIAN_CALLS = {"f32": bq.bpdq_hessian_accumulate_f32, "bf16x3": bq.bpdq_hessian_accumulate}
 
 
 @pytest.fixture(params=["f32", "bf16x3"])
@@ -111,7 +111,7 @@ def test_hessian_bf16x3_long_accumulation(dev):
     Href = np.zeros((d_in, d_in))
     orc.hessian_accumulate(X.numpy(), Href)
     H = torch.zeros((d_in, d_in), device=dev)
-    bq.bpdq_hessian_accumulate_bf16x3(X.to(dev), H, symmetrize=True)
+    bq.bpdq_hessian_accumulate(X.to(dev), H, symmetrize=True)
     Hg = H.cpu().numpy().astype(np.float64)
     assert _relfro(Hg, Href) < H_TOL
     scale = np.sqrt(np.outer(np.diag(Href), np.diag(Href)))
@@ -128,7 +128,7 @@ def test_hessian_bf16x3_host_split_launches(dev):
     X = torch.randn((n_tok, d_in), generator=g, device=dev)
     idx = torch.randperm(d_in, generator=torch.Generator().manual_seed(5))[:96].sort().values.to(dev)
     H = torch.zeros((d_in, d_in), device=dev)
-    bq.bpdq_hessian_accumulate_bf16x3(X, H, symmetrize=True)
+    bq.bpdq_hessian_accumulate(X, H, symmetrize=True)
     Hsub = np.zeros((96, 96))
     orc.hessian_accumulate(X[:, idx].cpu().numpy(), Hsub)
     Hg = H[idx][:, idx].cpu().numpy().astype(np.float64)
@@ -139,7 +139,7 @@ def test_hessian_bf16x3_host_split_launches(dev):
     d_in, n_tok = 8, 530000
     X = torch.randn((n_tok, d_in), generator=g, device=dev) * 3.0
     H = torch.zeros((d_in, d_in), device=dev)
-    bq.bpdq_hessian_accumulate_bf16x3(X, H, symmetrize=True)
+    bq.bpdq_hessian_accumulate(X, H, symmetrize=True)
     Href = np.zeros((d_in, d_in))
     orc.hessian_accumulate(X.cpu().numpy(), Href)
     assert _relfro(H.cpu().numpy().astype(np.float64), Href) < H_TOL

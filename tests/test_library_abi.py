@@ -65,10 +65,10 @@ def test_size_queries(lib):
 
 def test_argument_errors_are_reported_without_a_gpu(lib):
     # invalid arguments are rejected on the host before any HIP call
+    assert lib.bpdq_hessian_accumulate_f32(None, -1, 64, 64, 2.0, None, 0, None, 0, None) == -2
+    assert lib.bpdq_hessian_accumulate_f32(None, 0, 6, 64, 2.0, None, 0, None, 0, None) == -3
     assert lib.bpdq_hessian_accumulate(None, -1, 64, 64, 2.0, None, 0, None, 0, None) == -2
     assert lib.bpdq_hessian_accumulate(None, 0, 6, 64, 2.0, None, 0, None, 0, None) == -3
-    assert lib.bpdq_hessian_accumulate_bf16x3(None, -1, 64, 64, 2.0, None, 0, None, 0, None) == -2
-    assert lib.bpdq_hessian_accumulate_bf16x3(None, 0, 6, 64, 2.0, None, 0, None, 0, None) == -3
     assert lib.bpdq_prepare(None, 64, 0.01, None, None, None, None, 0, None) == -1
     assert lib.bpdq_pack_planes(None, 4, 64, 2, None, None) == -1
     assert lib.bpdq_dequant(None, None, 4, 64, 2, 32, None, None) == -1
