@@ -1,5 +1,5 @@
 """GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
-seeded inputs.  Tolerances (BASELINE the benchmark spec): H within 1e-5 relative Frobenius error;
+seeded inputs.  Tolerances (those of the benchmark definition): H within 1e-5 relative Frobenius error;
 layer objective within 1e-3 relative; at most 0.1 % of plane bits differing; packing bit-exact.
 """
 import numpy as np
