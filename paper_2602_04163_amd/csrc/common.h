@@ -19,6 +19,17 @@
     if (hipGetLastError() != hipSuccess) return BPDQ_ERR_LAUNCH; \
   } while (0)
 
+// Raises a kernel's dynamic-LDS limit once per process and kernel.  `bpdq_lds_limit<&kernel>(n)`
+// holds one function-local static per kernel (initialised under the language's own lock, so
+// concurrent first calls from several host threads are safe) and returns the HIP status of that
+// one-off call.
+template <auto KERNEL>
+static inline hipError_t bpdq_lds_limit(size_t bytes) {
+  static const hipError_t status = hipFuncSetAttribute(
+      reinterpret_cast<const void*>(KERNEL), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  return status;
+}
+
 static inline size_t bpdq_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 static inline int bpdq_ceil_div(int a, int b) { return (a + b - 1) / b; }
 

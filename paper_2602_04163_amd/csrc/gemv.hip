@@ -117,22 +117,16 @@ extern "C" int bpdq_gemv(const uint32_t* planes, const uint16_t* coefs_h, int d_
   const _Float16* ch = reinterpret_cast<const _Float16*>(coefs_h);
   int grid = bpdq_ceil_div(d_out, kGemvWaves * 2);   // 2 rows per wavefront and pass
   if (grid > 256) grid = 256;                        // one work-group per CU; each builds the table once
-  auto launch = [&](auto kern) -> int {
-    static bool attr_set = false;
-    if (!attr_set) {
-      BPDQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)kGemvLdsBytes));
-      attr_set = true;
-    }
+  auto launch = [&](auto kern, hipError_t limit) -> int {
+    BPDQ_HIP_TRY(limit);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kGemvThreads), lds, stream, planes, ch, d_out, d_in, group, x, y);
     BPDQ_LAUNCH_CHECK();
     return 0;
   };
   switch (bits) {
-    case 1: return launch(gemv_planes_kernel<1>);
-    case 2: return launch(gemv_planes_kernel<2>);
-    case 3: return launch(gemv_planes_kernel<3>);
-    default: return launch(gemv_planes_kernel<4>);
+    case 1: return launch(gemv_planes_kernel<1>, bpdq_lds_limit<&gemv_planes_kernel<1>>(lds));
+    case 2: return launch(gemv_planes_kernel<2>, bpdq_lds_limit<&gemv_planes_kernel<2>>(lds));
+    case 3: return launch(gemv_planes_kernel<3>, bpdq_lds_limit<&gemv_planes_kernel<3>>(lds));
+    default: return launch(gemv_planes_kernel<4>, bpdq_lds_limit<&gemv_planes_kernel<4>>(lds));
   }
 }

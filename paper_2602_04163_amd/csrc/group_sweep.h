@@ -880,12 +880,7 @@ struct UniformSweepArgs {
 template <int K, int G>
 static inline int launch_uniform_sweep(const UniformSweepArgs& a) {
   const size_t lds = sweep_lds_bytes<G>();
-  static bool attr_set = false;
-  if (!attr_set) {
-    BPDQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(uniform_group_kernel<K, G>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    attr_set = true;
-  }
+  BPDQ_HIP_TRY((bpdq_lds_limit<&uniform_group_kernel<K, G>>(lds)));
   hipLaunchKernelGGL((uniform_group_kernel<K, G>), dim3(a.grid), dim3(kSweepThreads), lds, a.stream,
                      a.Wp, a.d_in, a.d_out, a.U, a.d_in, a.s0, a.coef_fp16, a.c_codes, a.c_coef, a.c_E,
                      a.c_score, a.n_wg, a.Eall, a.lde, a.kp0, a.ta);
@@ -929,12 +924,7 @@ static inline int launch_group(hipStream_t stream, const float* Wp, int d_out, i
     else rc = launch_uniform_sweep<K, G>(a);
     if (rc) return rc;
   } else {
-    static bool attr_set = false;
-    if (!attr_set) {
-      BPDQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(bpdq_group_kernel<K, G>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-      attr_set = true;
-    }
+    BPDQ_HIP_TRY((bpdq_lds_limit<&bpdq_group_kernel<K, G>>(lds)));
     hipLaunchKernelGGL((bpdq_group_kernel<K, G>), dim3(grid), dim3(kSweepThreads), lds, stream,
                        Wp, d_in, d_out, U, d_in, s0, T, p.alpha, p.coef_fp16, c_codes, c_coef, c_E, c_score,
                        L.n_wg, Eall, L.lde, kp0, ta);

@@ -50,16 +50,18 @@ static double hess_makespan(int n_full, double c_full, int n_short, double c_sho
 // Measured: a sum of squares (the diagonal of H) accumulated by chained MFMAs comes out low, the
 // more so the longer the chain, as if the products of an instruction were truncated when aligned
 // to the running sum: about -1.3e-6 relative after 11 k tokens on the fp32 path, -4.5e-6 after
-// 52 k tokens and -2.5e-6 after 8 k tokens on the split path.  The split path therefore ends
-// every chain after kSplitChain tokens; the partial sums are added by ordinary round-to-nearest
+// 52 k tokens and -2.5e-6 after 8 k tokens on the split path.  Both paths therefore end every
+// chain after kChainTokens[kind] tokens; the partial sums are added by ordinary round-to-nearest
 // fp32 additions, which do not drift.
-constexpr int kSplitChain = 8192;
-constexpr int kSplitMaxSlices = 64;
+constexpr int kChainTokens[2] = {16384, 8192};
+constexpr int kMaxSlices = 64;
 
 // kind 0: fp32 MFMA kernel; kind 1: split-bf16 kernel (about 1.8 times the rate per token)
 static HessPlan plan_hessian(int n_tok, int d_in, int kind) {
-  static HessPlan cache[2];
-  static int cache_n[2] = {-1, -1}, cache_d[2] = {-1, -1};
+  // the last plan of each kind, per host thread (the search below costs a fraction of a millisecond,
+  // which a stream of short calls would otherwise pay every time)
+  thread_local HessPlan cache[2];
+  thread_local int cache_n[2] = {-1, -1}, cache_d[2] = {-1, -1};
   if (n_tok == cache_n[kind] && d_in == cache_d[kind]) return cache[kind];
   HessPlan p;
   p.nb = bpdq_ceil_div(d_in, HessGemm::kTileM);
@@ -72,9 +74,9 @@ static HessPlan plan_hessian(int n_tok, int d_in, int kind) {
     // per-token MFMA time of one 256 x 256 tile, fixed cost per work-group, cost per partial tile
     const double us_per_tok = kind ? 0.14 : 0.26, us_fixed = 8.0, us_per_partial = 0.131;
     const double diag_frac = 0.64;
-    const int s_max = n_tok / 256 < kSplitMaxSlices ? (n_tok / 256 < 1 ? 1 : n_tok / 256) : kSplitMaxSlices;
-    // the split kernel keeps every accumulation chain short (see kSplitChain)
-    int s_min = kind ? bpdq_ceil_div(n_tok, kSplitChain) : 1;
+    const int s_max = n_tok / 256 < kMaxSlices ? (n_tok / 256 < 1 ? 1 : n_tok / 256) : kMaxSlices;
+    // every accumulation chain stays short (see kChainTokens)
+    int s_min = bpdq_ceil_div(n_tok, kChainTokens[kind]);
     if (s_min > s_max) s_min = s_max;
     double best = 1e300;
     for (int So = s_min; So <= s_max; ++So) {
@@ -246,14 +248,14 @@ __global__ __launch_bounds__(256) void symmetrize_kernel(float* __restrict__ H, 
 
 using namespace bpdq;
 
-// Tokens of the next launch.  The fp32 path takes a chunk whole.  The split path bounds the chain
-// length: a launch that adds straight into H (no slices) takes kSplitChain tokens, a sliced one
-// as many as its slices can cover; successive launches on one stream accumulate in order.
+// Tokens of the next launch: the chain length is bounded (kChainTokens).  A launch that adds
+// straight into H (no slices) takes one chain's worth of tokens, a sliced one as many as its
+// slices can cover; successive launches on one stream accumulate in order.
 static int hessian_launch_tokens(int kind, int n_left, int d_in) {
-  if (kind == 0) return n_left;
-  const long cover = (long)kSplitChain * kSplitMaxSlices;
+  const int chain = kChainTokens[kind];
+  const long cover = (long)chain * kMaxSlices;
   int n = n_left > cover ? (int)cover : n_left;
-  if (n > kSplitChain && plan_hessian(n, d_in, kind).direct) n = kSplitChain;
+  if (n > chain && plan_hessian(n, d_in, kind).direct) n = chain;
   return n;
 }
 
@@ -278,16 +280,8 @@ static int hessian_accumulate(int kind, const float* Xc, int n_tok, int d_in, in
     const HessPlan p = plan_hessian(n_part, d_in, kind);
     const float* Xpart = Xc + (long)done * ldx;
     done += n_part;
-    static bool attr_set = false;
-    if (!attr_set) {
-      BPDQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(hess_syrk_f32_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)HessGemm::kLdsBytes));
-      BPDQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(hess_syrk_bf16x3_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)SplitSyrk::kLdsBytes));
-      attr_set = true;
-    }
+    BPDQ_HIP_TRY(bpdq_lds_limit<&hess_syrk_f32_kernel>(HessGemm::kLdsBytes));
+    BPDQ_HIP_TRY(bpdq_lds_limit<&hess_syrk_bf16x3_kernel>(SplitSyrk::kLdsBytes));
     if (kind == 0) {
       hipLaunchKernelGGL(hess_syrk_f32_kernel, dim3(p.items()), dim3(HessGemm::kThreads),
                          HessGemm::kLdsBytes, stream, Xpart, n_part, d_in, (long)ldx, scale, H,

@@ -668,13 +668,7 @@ extern "C" int bpdq_prepare(const float* H, int d_in, float damp, float* U, unsi
   double* R12buf = reinterpret_cast<double*>(base + L.r12_off);
   int* pair_flag = reinterpret_cast<int*>(base + L.flag_off);
   const int d = d_in, P = L.P;
-  static bool attr_set = false;
-  if (!attr_set) {
-    BPDQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(panel_pair_kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     (int)kPairLdsBytes));
-    attr_set = true;
-  }
+  BPDQ_HIP_TRY(bpdq_lds_limit<&panel_pair_kernel>(kPairLdsBytes));
 
   hipLaunchKernelGGL(prep_diag_kernel, dim3(1), dim3(1024), 0, stream, H, d, damp, dead, scal, info);
   BPDQ_LAUNCH_CHECK();

@@ -14,13 +14,7 @@ __global__ __launch_bounds__(TailGemm::kThreads) void tail_update_kernel(TailArg
 
 int launch_tail_update(hipStream_t stream, TailArgs ta, const float* U, int ldu, int lde, int ldw,
                        int d_out, int n_tiles) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    BPDQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(tail_update_kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     (int)TailGemm::kLdsBytes));
-    attr_set = true;
-  }
+  BPDQ_HIP_TRY(bpdq_lds_limit<&tail_update_kernel>(TailGemm::kLdsBytes));
   ta.first_wg = 0;
   hipLaunchKernelGGL(tail_update_kernel, dim3(n_tiles), dim3(TailGemm::kThreads), TailGemm::kLdsBytes,
                      stream, ta, U, ldu, lde, ldw, d_out);
