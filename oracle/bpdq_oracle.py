@@ -96,12 +96,15 @@ def prepare(H, damp=0.01):
 # --------------------------------------------------------------------------- #
 # Step 3a: bit-plane initialisation  (Sec. 3.2 "Bit-Plane Selection", Eq. 5)
 # --------------------------------------------------------------------------- #
-def init_codes(T, k, decision_dtype=np.float32):
+def init_codes(T, k, decision_dtype=np.float32, margins=None):
     """Per row: affine round-to-nearest of the group to Z in 0..255, keep the k
     most significant planes.  Returns code = Z >> (8-k) as uint8 (rows x g); bit
     (i-1) of code is plane B_i.
     Operation order (in decision_dtype): sc = (hi - lo) / 255; q = (t - lo) / sc;
-    Z = clamp(round_half_even(q), 0, 255)."""
+    Z = clamp(round_half_even(q), 0, 255).
+    `margins` (rows,), if given, is lowered to the smallest distance (in weight units) of any
+    weight of the row from a rounding boundary that separates two kept codes (instrumentation
+    for the parity tests: how close a decision came to a tie; the result does not depend on it)."""
     dt = np.float64 if decision_dtype is None else decision_dtype
     t = np.asarray(T).astype(dt)
     lo = t.min(axis=1, keepdims=True)
@@ -112,6 +115,12 @@ def init_codes(T, k, decision_dtype=np.float32):
     q = (t - lo) / sc_safe
     Z = np.clip(np.rint(q), 0, 255).astype(np.int64)
     Z = np.where(flat, 0, Z)
+    if margins is not None:
+        step = 1 << (8 - k)                       # Z values per kept code
+        bounds = np.arange(1, 1 << k) * step - 0.5
+        dist = np.abs(q.astype(np.float64)[:, :, None] - bounds[None, None, :]).min(axis=(1, 2))
+        dist = np.where(flat[:, 0], np.inf, dist * sc_safe[:, 0].astype(np.float64))
+        np.minimum(margins, dist, out=margins)
     return (Z >> (8 - k)).astype(np.uint8)
 
 
@@ -183,12 +192,15 @@ def nearest_level(w, lv):
     return np.argmin(dist, axis=1)          # first minimum = lowest code
 
 
-def bitplane_sweep(T, UL, c, k, decision_dtype=np.float32):
+def bitplane_sweep(T, UL, c, k, decision_dtype=np.float32, margins=None):
     """One column-by-column pass over a group with fixed coefficients c.
     Starts from the group-start working block T; at each column picks the
     nearest level per row, forms the error coordinate (Eq. 3) and compensates
     the remaining columns of the group (Eq. 4).
-    Returns (code, What_old, E), each rows x g."""
+    Returns (code, What_old, E), each rows x g.
+    `margins` (rows,), if given, is lowered to the smallest gap between the distances of the
+    working weight to its nearest and to its second nearest *distinct* level value met in this
+    pass (instrumentation for the parity tests; the result does not depend on it)."""
     T = np.asarray(T, dtype=np.float64)
     rows, g = T.shape
     Wg = T.copy()
@@ -202,6 +214,11 @@ def bitplane_sweep(T, UL, c, k, decision_dtype=np.float32):
     for l in range(g):
         sel = nearest_level(Wg[:, l].astype(dt), lvd)
         code[:, l] = sel
+        if margins is not None:
+            gap = np.abs(Wg[:, l][:, None] - lv64)
+            best = gap[ar, sel][:, None]
+            other = np.where(lv64 != lv64[ar, sel][:, None], gap, np.inf).min(axis=1)
+            np.minimum(margins, other - best[:, 0], out=margins)
         What[:, l] = lv64[ar, sel]
         E[:, l] = (Wg[:, l] - What[:, l]) / UL[l, l]
         Wg[:, l + 1:] -= np.outer(E[:, l], UL[l, l + 1:])
@@ -222,25 +239,32 @@ def solve_right(R, UL):
 # Step 3 for one group: init, fit, iterate, keep the best iterate (Sec. 3.2, 3.3)
 # --------------------------------------------------------------------------- #
 def bpdq_group(T, UL, k, refine_iters, alpha=1e-4, select_per_row=False,
-               decision_dtype=np.float32, trace=None, coef_dtype=None):
+               decision_dtype=np.float32, trace=None, coef_dtype=None, margins=None,
+               forced_iter=None):
     """Quantize one group given its group-start working block T (rows x g) and
     the local factor UL.  Returns dict(code, coef, What, E, score, it):
     E is the propagation coordinate block consistent with the returned What
     (T - What = E @ UL), score = ||E||_F^2 (scalar, or per row when
-    select_per_row), it = index of the retained iterate (0 = initialisation)."""
+    select_per_row), it = index of the retained iterate (0 = initialisation).
+    Test instrumentation: `margins` (rows,) collects the closest call of any decision of the
+    row (see init_codes, bitplane_sweep); `forced_iter` = t returns iterate t instead of the
+    one with the smallest score (used when rows are sampled from a larger layer whose
+    group-wise choice they cannot reproduce on their own); the scores of all iterates are
+    returned as `scores`."""
     T = np.asarray(T, dtype=np.float64)
     rows, g = T.shape
-    code = init_codes(T, k, decision_dtype)
+    code = init_codes(T, k, decision_dtype, margins)
     c = round_coefficients(fit_coefficients(code, T, UL, k, alpha), coef_dtype)
     What = reconstruct(code, c, k)
     E = solve_right(T - What, UL)
     rs = np.sum(E * E, axis=1)
     best = dict(code=code, coef=c, What=What, E=E, rowscore=rs,
                 it=np.zeros(rows, dtype=np.int32))
+    scores = [float(rs.sum())]
     if trace is not None:
         trace.append(dict(it=0, score=float(rs.sum()), rowscore=rs.copy()))
     for t in range(1, refine_iters + 1):
-        code_t, What_old, E_t = bitplane_sweep(T, UL, c, k, decision_dtype)
+        code_t, What_old, E_t = bitplane_sweep(T, UL, c, k, decision_dtype, margins)
         c = round_coefficients(fit_coefficients(code_t, T, UL, k, alpha), coef_dtype)  # refit, Sec. 3.3
         What_new = reconstruct(code_t, c, k)
         dE = solve_right(What_old - What_new, UL)                     # Eq. 9
@@ -250,7 +274,10 @@ def bpdq_group(T, UL, k, refine_iters, alpha=1e-4, select_per_row=False,
             trace.append(dict(it=t, score=float(rs.sum()), rowscore=rs.copy(),
                               code=code_t.copy(), What_old=What_old, What_new=What_new,
                               E_sweep=E_t, E_corr=Ep, coef=c.copy()))
-        if select_per_row:
+        scores.append(float(rs.sum()))
+        if forced_iter is not None:
+            take = np.full(rows, t == int(forced_iter))
+        elif select_per_row:
             take = rs < best["rowscore"]
         else:
             take = np.full(rows, rs.sum() < best["rowscore"].sum())
@@ -260,10 +287,11 @@ def bpdq_group(T, UL, k, refine_iters, alpha=1e-4, select_per_row=False,
                 best[key] = np.where(take.reshape((-1,) + (1,) * (val.ndim - 1)), val, best[key])
             best["it"] = np.where(take, t, best["it"]).astype(np.int32)
     best["score"] = best["rowscore"] if select_per_row else float(best["rowscore"].sum())
+    best["scores"] = np.asarray(scores)
     return best
 
 
-def uniform_frozen_group(T, UL, k, decision_dtype=np.float32, coef_dtype=None):
+def uniform_frozen_group(T, UL, k, decision_dtype=np.float32, coef_dtype=None, margins=None):
     """The fixed uniform grid written as a variable grid (App. A, Prop. 1): coefficients frozen
     to (lo, s, 2s, 4s, ...), s = (hi - lo) / (2^k - 1) from the group-start block's per-row
     min / max (a flat row gets s = 1), one bit-plane update pass, no fit, no iteration.  This is
@@ -276,7 +304,7 @@ def uniform_frozen_group(T, UL, k, decision_dtype=np.float32, coef_dtype=None):
     s = np.where(s == 0.0, 1.0, s)
     c = np.stack([lo] + [s * (1 << i) for i in range(k)], axis=1)
     c = round_coefficients(c, coef_dtype)
-    code, What, E = bitplane_sweep(T, UL, c, k, decision_dtype)
+    code, What, E = bitplane_sweep(T, UL, c, k, decision_dtype, margins)
     return dict(code=code, coef=c, What=What, E=E, it=np.zeros(T.shape[0], dtype=np.int32))
 
 
@@ -285,7 +313,7 @@ def uniform_frozen_group(T, UL, k, decision_dtype=np.float32, coef_dtype=None):
 # --------------------------------------------------------------------------- #
 def quantize_layer(W, U, dead, bits, group, block, refine_iters, alpha=1e-4,
                    select_per_row=False, decision_dtype=np.float32, group_fn=None, progress=None,
-                   coef_dtype=None):
+                   coef_dtype=None, forced_iter=None):
     """Sweep the columns of W block by block (Sec. 3.1 compensation; App. B.3 tail
     form).  Returns dict with
       code   uint8  (d_out x d_in)     plane bits, bit (i-1) = B_i
@@ -297,7 +325,8 @@ def quantize_layer(W, U, dead, bits, group, block, refine_iters, alpha=1e-4,
       objective = sum grp_err  (= tr((W-What) Ht (W-What)^T), App. B.2)
     `group_fn(T, UL)` may replace the BPDQ group solver (used for the
     fixed-uniform-grid comparison of App. A).  `progress(b1, d_in)`, if given, is called after
-    every block (long runs report where they are)."""
+    every block (long runs report where they are).  `forced_iter` (d_in/g ints), if given, fixes
+    the retained iterate of every group (see bpdq_group)."""
     Wp = np.array(W, dtype=np.float64)
     U = np.asarray(U, dtype=np.float64)
     d_out, d_in = Wp.shape
@@ -316,16 +345,18 @@ def quantize_layer(W, U, dead, bits, group, block, refine_iters, alpha=1e-4,
     Eall = np.zeros((d_out, d_in))
     grp_err = np.zeros(ngrp)
     grp_iter = np.zeros((d_out, ngrp) if select_per_row else ngrp, dtype=np.int32)
+    forced = [None]
     if group_fn is None:
         def group_fn(T, UL):
             return bpdq_group(T, UL, k, refine_iters, alpha, select_per_row, decision_dtype,
-                              coef_dtype=coef_dtype)
+                              coef_dtype=coef_dtype, forced_iter=forced[0])
     for b0 in range(0, d_in, B):
         b1 = min(b0 + B, d_in)
         for s in range(b0, b1, g):
             gi = s // g
             T = Wp[:, s:s + g].copy()
             UL = U[s:s + g, s:s + g]
+            forced[0] = None if forced_iter is None else int(forced_iter[gi])
             res = group_fn(T, UL)
             code[:, s:s + g] = res["code"]
             coef[:, :, gi] = np.asarray(res["coef"]).T
