@@ -192,6 +192,16 @@ int bpdq_gemv(const uint32_t* planes, const uint16_t* coefs_h, int d_out, int d_
 size_t bpdq_channel_order_workspace_bytes(int d_in);
 int bpdq_channel_order(const float* H, int d_in, int group_size, int* perm, void* ws,
                        size_t ws_bytes, void* stream);
+/* bpdq_channel_order for callers that cannot allocate device memory and have no workspace to
+ * hand over (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc):
+ * same arguments and result, the sort keys live in a 256 KB device array built into the library
+ * (one copy per GPU, held until the process ends).  No hipMalloc / hipFree, no workspace.
+ *   Limit: d_in / group_size <= 32768 keys; more returns -2 and launches nothing.
+ *   All calls on one GPU share that array: calls that may overlap on one GPU (different streams,
+ *   different host threads) race and must be serialised by the caller.  Nothing of an earlier
+ *   call's contents enters a later result.
+ * Returns 0, -1 H, -2 d_in (or too many keys), -3 group_size, -4 perm, BPDQ_ERR_LAUNCH. */
+int bpdq_channel_order_noalloc(const float* H, int d_in, int group_size, int* perm, void* stream);
 int bpdq_gather_columns(const float* W, int d_out, int d_in, const int* perm, float* Wp,
                         void* stream);
 int bpdq_scatter_columns(const float* Wp, int d_out, int d_in, const int* perm, float* W,

@@ -21,7 +21,8 @@ EXPORTS = [
     "bpdq_prepare_workspace_bytes", "bpdq_prepare",
     "bpdq_quantize_workspace_bytes", "bpdq_quantize_layer", "bpdq_quantize_layers",
     "bpdq_pack_planes", "bpdq_dequant", "bpdq_coefs_to_fp16", "bpdq_dequant_fp16",
-    "bpdq_channel_order_workspace_bytes", "bpdq_channel_order", "bpdq_gather_columns",
+    "bpdq_channel_order_workspace_bytes", "bpdq_channel_order", "bpdq_channel_order_noalloc",
+    "bpdq_gather_columns",
     "bpdq_scatter_columns", "bpdq_gather_symmetric", "bpdq_gemv",
 ]
 
@@ -80,6 +81,8 @@ def load():
     lib.bpdq_channel_order_workspace_bytes.argtypes = [ci]
     lib.bpdq_channel_order.restype = ci
     lib.bpdq_channel_order.argtypes = [vp, ci, ci, vp, vp, sz, vp]
+    lib.bpdq_channel_order_noalloc.restype = ci
+    lib.bpdq_channel_order_noalloc.argtypes = [vp, ci, ci, vp, vp]
     lib.bpdq_gather_columns.restype = ci
     lib.bpdq_gather_columns.argtypes = [vp, ci, ci, vp, vp, vp]
     lib.bpdq_scatter_columns.restype = ci
@@ -293,6 +296,20 @@ def bpdq_channel_order(H, group_size=1):
     ws = _workspace(lib.bpdq_channel_order_workspace_bytes(d_in), H.device)
     _check(lib.bpdq_channel_order(_ptr(H), d_in, group_size, _ptr(perm), _ptr(ws), ws.numel(),
                                   _stream()), "bpdq_channel_order")
+    return perm
+
+
+def bpdq_channel_order_noalloc(H, group_size=1, perm=None):
+    """bpdq_channel_order without a workspace: the library's built-in scratch holds the keys.
+    `perm` may be passed in, so that the call allocates nothing at all."""
+    lib = load()
+    _dev(H, torch.float32, "H")
+    d_in = H.shape[0]
+    if perm is None:
+        perm = torch.empty(d_in, dtype=torch.int32, device=H.device)
+    _dev(perm, torch.int32, "perm")
+    _check(lib.bpdq_channel_order_noalloc(_ptr(H), d_in, group_size, _ptr(perm), _stream()),
+           "bpdq_channel_order_noalloc")
     return perm
 
 

@@ -2,9 +2,17 @@
 // of the Hessian diagonal; BPDQ's experiments use a group-preserving reordering).  The pass
 // itself always runs left to right; these helpers build a permutation and move W / H / W_hat in
 // and out of the permuted order.
+#include <mutex>
+
 #include "common.h"
 
 namespace bpdq {
+
+// Scratch of bpdq_channel_order_noalloc: the sort keys, one double per block of channels.  A
+// device-resident array of the library itself, so that the call needs no workspace and no
+// allocation; every GPU the library runs on holds its own copy (256 KB) until the process ends.
+constexpr int kOrderNoAllocMaxKeys = 32768;
+static __device__ __align__(256) double scratch[kOrderNoAllocMaxKeys];
 
 // key[b] = sum of H_jj over block b of `gs` consecutive channels, fp64, index order
 __global__ __launch_bounds__(256) void order_key_kernel(const float* __restrict__ H, int d, int gs,
@@ -90,6 +98,49 @@ extern "C" int bpdq_channel_order(const float* H, int d_in, int group_size, int*
   if (!ws || (reinterpret_cast<uintptr_t>(ws) & 7)) return -5;
   if (ws_bytes < bpdq_channel_order_workspace_bytes(d_in)) return -6;
   double* key = static_cast<double*>(ws);
+  const int n = d_in / group_size;
+  hipLaunchKernelGGL(order_key_kernel, dim3(bpdq_ceil_div(n, 256)), dim3(256), 0, stream, H, d_in,
+                     group_size, key);
+  BPDQ_LAUNCH_CHECK();
+  hipLaunchKernelGGL(order_rank_kernel, dim3(bpdq_ceil_div(n, 256)), dim3(256), 0, stream, key, n,
+                     group_size, perm);
+  BPDQ_LAUNCH_CHECK();
+  return 0;
+}
+
+// Device address of `scratch` on the current GPU.  In host code the array's name is only a handle
+// for the runtime; the address is looked up once per device (with that device current) and kept.
+static int order_scratch(double** out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex lock;
+  static double* ptr[kMaxDevices] = {};
+  int dev = -1;
+  BPDQ_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return BPDQ_ERR_LAUNCH;
+  std::lock_guard<std::mutex> guard(lock);
+  if (!ptr[dev]) {
+    double* p = nullptr;
+    BPDQ_HIP_TRY(hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch)));
+    if (!p) return BPDQ_ERR_LAUNCH;
+    ptr[dev] = p;
+  }
+  *out = ptr[dev];
+  return 0;
+}
+
+extern "C" int bpdq_channel_order_noalloc(const float* H, int d_in, int group_size, int* perm,
+                                          void* stream_) {
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  if (!H) return -1;
+  if (d_in <= 0) return -2;
+  if (group_size < 1 || d_in % group_size) return -3;
+  if (d_in / group_size > kOrderNoAllocMaxKeys) return -2;      // beyond the built-in scratch
+  if (!perm) return -4;
+  double* key = nullptr;
+  const int rc = order_scratch(&key);
+  if (rc) return rc;
+  // every key the second kernel reads is written by the first: nothing of the previous call's
+  // contents survives into the result
   const int n = d_in / group_size;
   hipLaunchKernelGGL(order_key_kernel, dim3(bpdq_ceil_div(n, 256)), dim3(256), 0, stream, H, d_in,
                      group_size, key);
