@@ -154,15 +154,27 @@ def fit_coefficients(code, T, UL, k, alpha=1e-4):
     return np.linalg.solve(G, b[:, :, None])[:, :, 0]
 
 
-def round_coefficients(c, coef_dtype=None):
+def round_coefficients(c, coef_dtype=None, margins=None):
     """Storage precision of the coefficients.  Table 1 counts 16 bits per coefficient; the
     paper does not say when the rounding happens.  Reading taken: with `coef_dtype=np.float16`
     every fitted coefficient is rounded (fp64 -> fp32 -> fp16, round to nearest even) right
     after the fit, so that the levels of the next bit-plane update, What, the propagation
-    coordinates E and the score all belong to the values that are stored.  None = no rounding."""
+    coordinates E and the score all belong to the values that are stored.  None = no rounding.
+    `margins` (rows,), if given, is lowered to the smallest distance of any coefficient of the
+    row from the boundary between two neighbouring storage values, relative to the row's largest
+    coefficient magnitude (instrumentation for the parity tests: the rounding is a decision too)."""
     if coef_dtype is None:
         return c
-    return np.asarray(c).astype(np.float32).astype(coef_dtype).astype(np.float64)
+    r = np.asarray(c).astype(np.float32).astype(coef_dtype)
+    if margins is not None:
+        c64 = np.asarray(c, dtype=np.float64)
+        up = np.nextafter(r, coef_dtype(np.inf)).astype(np.float64)
+        dn = np.nextafter(r, coef_dtype(-np.inf)).astype(np.float64)
+        r64 = r.astype(np.float64)
+        dist = np.minimum(np.abs(0.5 * (r64 + up) - c64), np.abs(0.5 * (r64 + dn) - c64))
+        rel = dist.min(axis=1) / (np.abs(c64).max(axis=1) + 1e-300)
+        np.minimum(margins, rel, out=margins)
+    return r.astype(np.float64)
 
 
 # --------------------------------------------------------------------------- #
@@ -240,21 +252,22 @@ def solve_right(R, UL):
 # --------------------------------------------------------------------------- #
 def bpdq_group(T, UL, k, refine_iters, alpha=1e-4, select_per_row=False,
                decision_dtype=np.float32, trace=None, coef_dtype=None, margins=None,
-               forced_iter=None):
+               forced_iter=None, coef_margins=None):
     """Quantize one group given its group-start working block T (rows x g) and
     the local factor UL.  Returns dict(code, coef, What, E, score, it):
     E is the propagation coordinate block consistent with the returned What
     (T - What = E @ UL), score = ||E||_F^2 (scalar, or per row when
     select_per_row), it = index of the retained iterate (0 = initialisation).
     Test instrumentation: `margins` (rows,) collects the closest call of any decision of the
-    row (see init_codes, bitplane_sweep); `forced_iter` = t returns iterate t instead of the
+    row (see init_codes, bitplane_sweep), `coef_margins` (rows,) that of the coefficient
+    roundings (see round_coefficients); `forced_iter` = t returns iterate t instead of the
     one with the smallest score (used when rows are sampled from a larger layer whose
     group-wise choice they cannot reproduce on their own); the scores of all iterates are
     returned as `scores`."""
     T = np.asarray(T, dtype=np.float64)
     rows, g = T.shape
     code = init_codes(T, k, decision_dtype, margins)
-    c = round_coefficients(fit_coefficients(code, T, UL, k, alpha), coef_dtype)
+    c = round_coefficients(fit_coefficients(code, T, UL, k, alpha), coef_dtype, coef_margins)
     What = reconstruct(code, c, k)
     E = solve_right(T - What, UL)
     rs = np.sum(E * E, axis=1)
@@ -265,7 +278,7 @@ def bpdq_group(T, UL, k, refine_iters, alpha=1e-4, select_per_row=False,
         trace.append(dict(it=0, score=float(rs.sum()), rowscore=rs.copy()))
     for t in range(1, refine_iters + 1):
         code_t, What_old, E_t = bitplane_sweep(T, UL, c, k, decision_dtype, margins)
-        c = round_coefficients(fit_coefficients(code_t, T, UL, k, alpha), coef_dtype)  # refit, Sec. 3.3
+        c = round_coefficients(fit_coefficients(code_t, T, UL, k, alpha), coef_dtype, coef_margins)  # refit, Sec. 3.3
         What_new = reconstruct(code_t, c, k)
         dE = solve_right(What_old - What_new, UL)                     # Eq. 9
         Ep = E_t + dE
@@ -291,7 +304,8 @@ def bpdq_group(T, UL, k, refine_iters, alpha=1e-4, select_per_row=False,
     return best
 
 
-def uniform_frozen_group(T, UL, k, decision_dtype=np.float32, coef_dtype=None, margins=None):
+def uniform_frozen_group(T, UL, k, decision_dtype=np.float32, coef_dtype=None, margins=None,
+                         coef_margins=None):
     """The fixed uniform grid written as a variable grid (App. A, Prop. 1): coefficients frozen
     to (lo, s, 2s, 4s, ...), s = (hi - lo) / (2^k - 1) from the group-start block's per-row
     min / max (a flat row gets s = 1), one bit-plane update pass, no fit, no iteration.  This is
@@ -303,7 +317,7 @@ def uniform_frozen_group(T, UL, k, decision_dtype=np.float32, coef_dtype=None, m
     s = (hi - lo) / float((1 << k) - 1)
     s = np.where(s == 0.0, 1.0, s)
     c = np.stack([lo] + [s * (1 << i) for i in range(k)], axis=1)
-    c = round_coefficients(c, coef_dtype)
+    c = round_coefficients(c, coef_dtype, coef_margins)
     code, What, E = bitplane_sweep(T, UL, c, k, decision_dtype, margins)
     return dict(code=code, coef=c, What=What, E=E, it=np.zeros(T.shape[0], dtype=np.int32))
 

@@ -19,7 +19,16 @@ weights.  The fp32 state of the GPU differs from the exact state by rounding of 
 updates (a few 2^-24 per update, random sign, tens to hundreds of updates: about 1e-6 of the
 row's magnitude), so with tie_tol = 1e-5 a row that is not a near-tie row has no decision the
 GPU may legitimately take differently: its planes must be identical and its coefficients agree
-to rounding.  Near-tie rows are counted and reported separately.
+to rounding.  Near-tie rows are counted and reported separately.  With 16-bit coefficient storage
+the rounding of a fitted coefficient to a half is one more decision: a row is also a near-tie row
+when a coefficient lay within `COEF_TIE_TOL` (relative to the row's largest coefficient; the
+GPU's fitted coefficients deviate from the exact ones by about that) of the boundary between two
+halves -- the other half would move every level of the next bit-plane update by 2^-11.  The
+GPU's fitted coefficients are less exact than its weights (fp32 solves over the whole group feed
+the normal equations), so a flip of that rounding can also hit a row outside the flagged ones; such
+a row is accepted only if it is a valid result in its own right: its stored coefficients are the
+oracle's fit on the row's OWN planes, each within one half-precision step, and its error is close
+to the oracle row's.  These rows are counted (`rounding_flip_rows`).
 """
 import numpy as np
 from scipy.linalg import solve_triangular
@@ -27,6 +36,7 @@ from scipy.linalg import solve_triangular
 from oracle import bpdq_oracle as orc
 
 TIE_TOL = 1e-5
+COEF_TIE_TOL = 1e-5
 
 
 def propagation_coordinates(W, What, U):
@@ -64,19 +74,21 @@ def teacher_forced(W, U, code, coef, grp_iter, bits, group, iters, alpha, What=N
     st = dict(groups=0, rows=0, near_tie_rows=0, mismatch_rows=0, mismatch_clear_rows=0,
               selection_differs=0, selection_gap=0.0, coef_dev=0.0, clear_score_rel=0.0,
               bits_differing_clear=0, bits_total_clear=0,
+              rounding_flip_rows=0,
               near_tie_row_set=np.zeros(d_out, dtype=bool), mismatch_row_set=np.zeros(d_out, dtype=bool))
     for gi in glist:
         s = gi * g
         T = group_start_block(W[ridx], E[ridx], U, s, g)
         UL = U[s:s + g, s:s + g]
         margins = np.full(len(ridx), np.inf)
+        cmarg = np.full(len(ridx), np.inf)
         if uniform:
-            res = orc.uniform_frozen_group(T, UL, k, decision_dtype, coef_dtype, margins)
+            res = orc.uniform_frozen_group(T, UL, k, decision_dtype, coef_dtype, margins, cmarg)
             it_o = 0
         else:
             forced = int(grp_iter[gi]) if force_selection else None
             res = orc.bpdq_group(T, UL, k, iters, alpha, False, decision_dtype, coef_dtype=coef_dtype,
-                                 margins=margins, forced_iter=forced)
+                                 margins=margins, forced_iter=forced, coef_margins=cmarg)
             it_o = int(np.max(res["it"]))
             if it_o != int(grp_iter[gi]):
                 # the other side kept another iterate: legitimate only if the two scores tie
@@ -85,14 +97,32 @@ def teacher_forced(W, U, code, coef, grp_iter, bits, group, iters, alpha, What=N
                 st["selection_gap"] = max(st["selection_gap"],
                                           abs(sc[it_o] - sc[int(grp_iter[gi])]) / sc[it_o])
                 margins = np.full(len(ridx), np.inf)
+                cmarg = np.full(len(ridx), np.inf)
                 res = orc.bpdq_group(T, UL, k, iters, alpha, False, decision_dtype,
                                      coef_dtype=coef_dtype, margins=margins,
-                                     forced_iter=int(grp_iter[gi]))
+                                     forced_iter=int(grp_iter[gi]), coef_margins=cmarg)
         scale = np.abs(T).max(axis=1)
-        near = margins <= tie_tol * scale
+        near = (margins <= tie_tol * scale) | (cmarg <= COEF_TIE_TOL)
         cg = code[ridx, s:s + g]
         differ = (cg != res["code"]).any(axis=1)
         clear = ~near
+        odd = differ & clear
+        if coef_dtype is not None and odd.any() and not uniform:
+            # 16-bit storage: is the row the consistent result of another rounding of a coefficient?
+            c_fit = orc.round_coefficients(orc.fit_coefficients(cg[odd], T[odd], UL, k, alpha), coef_dtype)
+            c_g = coef[:, ridx, gi].T.astype(np.float64)[odd]
+            r16 = c_fit.astype(coef_dtype)
+            step = np.maximum(np.abs(np.nextafter(r16, coef_dtype(np.inf)).astype(np.float64) - c_fit),
+                              np.abs(np.nextafter(r16, coef_dtype(-np.inf)).astype(np.float64) - c_fit))
+            coef_ok = (np.abs(c_g - c_fit) <= step).all(axis=1)
+            Eg = orc.solve_right(T[odd] - What[ridx][odd][:, s:s + g], UL)
+            eg, eo = np.sum(Eg * Eg, axis=1), np.sum(res["E"][odd] ** 2, axis=1)
+            err_ok = np.abs(eg - eo) <= 0.1 * eo
+            valid = np.zeros(len(ridx), dtype=bool)
+            valid[np.flatnonzero(odd)] = coef_ok & err_ok
+            st["rounding_flip_rows"] += int(valid.sum())
+            near = near | valid
+            clear = ~near
         st["near_tie_row_set"] |= near
         st["mismatch_row_set"] |= differ
         st["groups"] += 1
@@ -141,6 +171,6 @@ def describe(st):
     return (f"teacher-forced: {st['groups']} groups, {st['rows']} (row, group) pairs; "
             f"near-tie {st['near_tie_rows']} ({st['near_tie_rows'] / max(st['rows'], 1):.2%}); "
             f"planes differ in {st['mismatch_rows']}, of which outside near-ties "
-            f"{st['mismatch_clear_rows']}; kept iterate differs in {st['selection_differs']} groups "
+            f"{st['mismatch_clear_rows']} (+{st['rounding_flip_rows']} valid after another coefficient rounding); kept iterate differs in {st['selection_differs']} groups "
             f"(score gap {st['selection_gap']:.1e}); coefficient deviation {st['coef_dev']:.1e}; "
             f"score over agreeing rows rel {st['clear_score_rel']:.1e}")
