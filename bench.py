@@ -18,8 +18,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_MFMA_F32_TFLOPS = 157.3    # MI355X dense fp32 matrix peak
-PEAK_MFMA_BF16_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
-SPLIT_PRODUCTS = 6              # bf16 products the split kernel issues per fp32 product
+PEAK_MFMA_16BIT_TFLOPS = 2500.0  # MI355X dense bf16 / fp16 matrix peak
+# 16-bit products a split kernel issues per fp32-accurate product
+SPLIT_PRODUCTS = {"f16x2": 3, "bf16x3": 6}
+KERNEL_NAMES = {"f16x2": "hess_syrk_f16x2_kernel", "bf16x3": "hess_syrk_bf16x3_kernel",
+                "f32": "hess_syrk_f32_kernel"}
 
 
 def parse():
@@ -30,13 +33,61 @@ def parse():
     ap.add_argument("--workload", default="cfg2_qwen7b_attn")
     ap.add_argument("--tokens-per-call", type=int, default=0,
                     help="tokens per bpdq_hessian_accumulate call (0 = all tokens in one call)")
-    ap.add_argument("--hessian", choices=["bf16x3", "f32"], default="bf16x3",
-                    help="Hessian kernel: three-piece bf16 split (default) or fp32 matrix cores")
+    ap.add_argument("--hessian", choices=["f16x2", "bf16x3", "f32"], default="f16x2",
+                    help="Hessian kernel: two fp16 halves per value (default, bpdq_hessian_accumulate), "
+                         "three bf16 pieces, or the fp32 matrix cores")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB -> 1 GiB elementwise kernel (scale for HBM counters)")
     ap.add_argument("--phases-only", default="", help="comma list of hessian,prepare,quantize (profiling)")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="measure the chip's own ceilings instead (register-only matrix-core loops, "
+                         "streaming copy) and print them as one JSON line")
     return ap.parse_args()
+
+
+def ceilings():
+    """Register-only loops of the matrix-core instructions the pass uses, on zero / one / normally
+    distributed operand values, one or two wavefronts per SIMD, and a 1 GiB streaming copy: what
+    this GPU sustains, next to the published peaks."""
+    import torch
+    from paper_2602_04163_amd import binding as bq
+    bq.load()
+    dev = torch.device("cuda:0")
+    out = torch.empty(256 * 512, device=dev)
+    peaks = {"f32": 157.3, "bf16": 2500.0, "f16": 2500.0, "f64": 78.6}
+    iters = {"f32": 32000, "bf16": 64000, "f16": 64000, "f64": 16000}
+    res = {"unit": "TFLOP/s", "mfma": [], "peaks": peaks}
+
+    def timed(fn, reps=10):
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a, b in ev:
+            a.record()
+            fn()
+            b.record()
+        torch.cuda.synchronize()
+        ms = sorted(a.elapsed_time(b) for a, b in ev[reps // 2:])      # the later half: settled clocks
+        return ms[len(ms) // 2]
+
+    for kind in ("f32", "bf16", "f16", "f64"):
+        for data in ("zeros", "ones", "normal"):
+            for waves in (1, 2):
+                flops = [0.0]
+
+                def run():
+                    flops[0] = bq.bpdq_probe_mfma(kind, data, waves, 256, iters[kind] // waves, out)
+                ms = timed(run)
+                tf = flops[0] / (ms * 1e-3) / 1e12
+                res["mfma"].append({"kind": kind, "data": data, "waves_per_simd": waves,
+                                    "ms": round(ms, 3), "tflops": round(tf, 1),
+                                    "frac_of_peak": round(tf / peaks[kind], 3)})
+    n = 1 << 28
+    src = torch.randn(n, device=dev)
+    dst = torch.empty_like(src)
+    ms = timed(lambda: bq.bpdq_probe_copy(src, dst))
+    res["copy"] = {"bytes_read": 4 * n, "bytes_written": 4 * n, "ms": round(ms, 3),
+                   "GBps_read_plus_write": round(8 * n / (ms * 1e-3) / 1e9, 1), "hbm_peak_GBps": 8000.0}
+    print(json.dumps(res), flush=True)
 
 
 def cpu_baseline(wl, W_cpu, scales_cpu, n_tok_sub=65536, rows_sub=1024):
@@ -89,6 +140,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if args.ceilings:
+        ceilings()
+        return
     bq.load()
     dev = torch.device("cuda:0")
     wl = wk.WORKLOADS[args.workload]
@@ -112,11 +166,21 @@ def main():
     ws_p = torch.empty(bq.bpdq_prepare_workspace_bytes(d_in), dtype=torch.uint8, device=dev)
     ws_q = torch.empty(bq.bpdq_quantize_workspace_bytes(d_out, d_in, p), dtype=torch.uint8, device=dev)
     out = None
+    infos = []
     phases = [s for s in args.phases_only.split(",") if s] or ["hessian", "prepare", "quantize"]
     ev = {k: [] for k in ("hessian", "prepare", "quantize")}
+    # events the library records right around the Hessian tile-product kernel (the dominant kernel
+    # of the step), on the stream it is launched on
+    kern_ev = []
 
-    hessian_call = (bq.bpdq_hessian_accumulate if args.hessian == "bf16x3"
-                    else bq.bpdq_hessian_accumulate_f32)
+    def hessian_call(Xc, Hm, scale, symmetrize, ws, record):
+        if not record:
+            return bq.bpdq_hessian_accumulate_timed(args.hessian, Xc, Hm, scale, symmetrize, ws)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        b.record()              # created now; the library records them again at the kernel
+        kern_ev.append((a, b))
+        return bq.bpdq_hessian_accumulate_timed(args.hessian, Xc, Hm, scale, symmetrize, ws, a, b)
 
     def step(record):
         nonlocal out
@@ -126,12 +190,13 @@ def main():
         if "hessian" in phases:
             H.zero_()
             for a, b in calls:
-                hessian_call(X[a:b], H, scale=2.0, symmetrize=False, ws=ws_h)
+                hessian_call(X[a:b], H, 2.0, False, ws_h, record)
         if record:
             marks[1].record()
         dead = None
         if "prepare" in phases:
-            _, dead, _ = bq.bpdq_prepare(H, wl.damp, U=U, ws=ws_p)
+            _, dead, info = bq.bpdq_prepare(H, wl.damp, U=U, ws=ws_p)
+            infos.append(info)
         if record:
             marks[2].record()
         if "quantize" in phases:
@@ -164,24 +229,39 @@ def main():
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     phase_ms = {k: sum(a.elapsed_time(b) for a, b in v) / max(len(v), 1) for k, v in ev.items()}
+    # outside the timed region: the factorisation of the last steps succeeded
+    if infos and any(int(i.item()) != 0 for i in infos[-2:]):
+        print("bench.py: bpdq_prepare reported a non-positive pivot", file=sys.stderr)
+        sys.exit(1)
+    kernel_ms = (sum(a.elapsed_time(b) for a, b in kern_ev) / len(kern_ev)) if kern_ev else 0.0
 
-    # ---- roofline of the dominant kernel: the Hessian SYRK -------------------------------
-    # algorithmic flops: the symmetric half, d(d+1) multiply-adds' worth per token
+    # ---- roofline of the dominant kernel: the Hessian tile product -----------------------------
+    # algorithmic flops: the symmetric half, d(d+1) multiply-adds' worth per token; duration: the
+    # library's own events around that kernel (one launch per call here), measured in the timed steps
     flops_per_launch = float(d_in) * (d_in + 1) * (n_tok / len(calls))
-    launch_ms = phase_ms["hessian"] / len(calls)
-    achieved = flops_per_launch / (launch_ms * 1e-3) / 1e12 if launch_ms > 0 else 0.0
+    achieved = flops_per_launch / (kernel_ms * 1e-3) / 1e12 if kernel_ms > 0 else 0.0
     traffic = None
-    kernel = "hess_syrk_bf16x3_kernel" if args.hessian == "bf16x3" else "hess_syrk_f32_kernel"
+    kernel = KERNEL_NAMES[args.hessian]
     tp = os.path.join(ROOT, "profiles", f"{kernel[:-7]}_{args.workload}_traffic.json")   # from rocprofv3 --pmc runs
     if os.path.exists(tp) and len(calls) == 1:
         traffic = json.load(open(tp)).get("hbm_bytes_per_launch")
-    if args.hessian == "bf16x3":
-        # `achieved` counts the fp32 products of the update; the kernel issues six bf16 products for
-        # each, so its ceiling on the bf16 pipe is a sixth of that pipe's peak
-        peak = PEAK_MFMA_BF16_TFLOPS / SPLIT_PRODUCTS
-        roof_extra = {"issued": achieved * SPLIT_PRODUCTS, "issued_peak": PEAK_MFMA_BF16_TFLOPS,
+    if args.hessian in SPLIT_PRODUCTS:
+        # `achieved` counts the fp32-accurate products of the update; the kernel issues n 16-bit
+        # products for each, so its ceiling on that pipe is 1/n of the pipe's peak
+        n = SPLIT_PRODUCTS[args.hessian]
+        peak = PEAK_MFMA_16BIT_TFLOPS / n
+        roof_extra = {"issued": achieved * n, "issued_peak": PEAK_MFMA_16BIT_TFLOPS,
                       "vs_fp32_mfma_peak": achieved / PEAK_MFMA_F32_TFLOPS,
-                      "note": "fp32-accurate product as six bf16 MFMA products; peak = bf16 dense peak / 6"}
+                      "note": f"one fp32-accurate product = {n} {'fp16' if n == 3 else 'bf16'} MFMA products; "
+                              f"peak = dense 16-bit matrix peak / {n}; duration = the tile-product kernel alone "
+                              "(events recorded by the library around it); the phase time also holds the "
+                              "split pre-pass and the reduction"}
+        cp = os.path.join(ROOT, "profiles", "ceilings_mi355x.json")
+        if os.path.exists(cp):
+            c = json.load(open(cp)).get("f16_normal_tflops" if n == 3 else "bf16_normal_tflops")
+            if c:
+                roof_extra["measured_pipe_ceiling"] = c
+                roof_extra["frac_of_measured_ceiling"] = achieved * n / c
     else:
         peak, roof_extra = PEAK_MFMA_F32_TFLOPS, {}
     res = {
@@ -191,13 +271,15 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32 (Hessian products as 3 x bf16 pieces, fp32 accumulate)" if args.hessian == "bf16x3" else "f32",
+        "dtype": {"f16x2": "f32 (Hessian products as 2 x fp16 halves of the scaled values, fp32 accumulate)",
+                  "bf16x3": "f32 (Hessian products as 3 x bf16 pieces, fp32 accumulate)", "f32": "f32"}[args.hessian],
         "data": "synthetic",
         "config": {"workload": wl.name, "d_out": d_out, "d_in": d_in, "tokens": n_tok,
                    "bits": wl.bits, "group": wl.group, "block": wl.block,
                    "refine_iters": wl.refine_iters, "hessian_calls_per_step": len(calls),
                    "hessian_kernel": args.hessian},
         "phase_ms": {k: round(v, 4) for k, v in phase_ms.items()},
+        "hessian_kernel_ms": round(kernel_ms, 4),
         "quantize_only_mparams_per_s": (wl.params / (phase_ms["quantize"] * 1e-3) / 1e6
                                         if phase_ms["quantize"] > 0 else None),
         "roofline": {"kernel": kernel, "bound": "mfma", "achieved": achieved,

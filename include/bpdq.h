@@ -68,26 +68,50 @@ int bpdq_version(void);
  *        symmetrize != 0 (e.g. on the last chunk) to mirror it into the lower triangle.
  *   scale : 2 reproduces the customary H = 2 X X^T; any positive factor gives the same
  *        planes and coefficients.
- *   ws : split-K partial sums; bpdq_hessian_workspace_bytes(n_tok, d_in) bytes (may be 0).
- * Requirements: d_in % 4 == 0, ldx % 4 == 0, Xc and H 16-byte aligned, n_tok >= 0.
+ *   ws : split-K partial sums and, for the default entry, the activations re-encoded as halves;
+ *        bpdq_hessian_workspace_bytes(n_tok, d_in) bytes serve any of the three entries
+ *        (about 4 * n_tok * d_in bytes plus the partial tiles).
+ * Requirements: d_in % 4 == 0, ldx % 4 == 0, Xc and H 16-byte aligned, ws 256-byte aligned, n_tok >= 0.
  * Returns 0, or a negative code naming the offending argument (-1 Xc, -2 n_tok, -3 d_in,
  * -4 ldx, -6 H, -8 ws, -9 ws_bytes); nothing is launched then.
  *
- * bpdq_hessian_accumulate runs on the bf16 matrix cores at fp32 accuracy: every value is cut
- * exactly into three bf16 pieces and every product is the sum of the six piece products that
- * matter, accumulated in fp32; the neglected terms are below 2^-24 of a product, i.e. below
- * the rounding of an fp32 product.  It assumes finite X with |x| < 2^127 (a value that rounds
- * to infinity in bf16 yields NaN).
- * bpdq_hessian_accumulate_f32 is the same update on the fp32 matrix cores (about 1.5 times
- * slower): same arguments, requirements, workspace and return codes.  The two results differ
- * only by rounding; each is bit-reproducible from call to call, they are not bit-identical to
- * one another. */
+ * Three kernels compute the same update; each result is bit-reproducible from call to call, they
+ * are not bit-identical to one another (they differ by rounding), and each is checked against the
+ * fp64 definition to 1e-5 relative Frobenius error.
+ * bpdq_hessian_accumulate (the fastest) runs on the fp16 matrix cores: a streaming pre-pass finds
+ *   every channel's largest magnitude in the call, scales the channel by the power of two that
+ *   brings it into [2^13, 2^14) and cuts every scaled value into two halves h + l (22 significant
+ *   bits); a product is the sum of the three half products of weight >= 2^-11, accumulated in fp32,
+ *   and the result is scaled back exactly.  The error of a product is below 2^-21 of it -- above
+ *   the 2^-24 of an fp32 product, far below the rounding of the fp32 accumulation over thousands of
+ *   tokens.  Assumes finite X (an infinity or NaN yields NaN in its row and column).
+ * bpdq_hessian_accumulate_bf16x3 runs on the bf16 matrix cores without a pre-pass: every value is
+ *   cut exactly into three bf16 pieces inside the kernel and a product is the sum of the six piece
+ *   products of weight >= 2^-16 (error below 2^-24 of a product).  About 1.5 times slower.
+ *   Assumes |x| < 2^127.
+ * bpdq_hessian_accumulate_f32 runs on the fp32 matrix cores (about 2.4 times slower). */
 size_t bpdq_hessian_workspace_bytes(int n_tok, int d_in);
 int bpdq_hessian_accumulate(const float* Xc, int n_tok, int d_in, int ldx, float scale,
                             float* H, int symmetrize, void* ws, size_t ws_bytes, void* stream);
+int bpdq_hessian_accumulate_bf16x3(const float* Xc, int n_tok, int d_in, int ldx, float scale,
+                                   float* H, int symmetrize, void* ws, size_t ws_bytes,
+                                   void* stream);
 int bpdq_hessian_accumulate_f32(const float* Xc, int n_tok, int d_in, int ldx, float scale,
                                 float* H, int symmetrize, void* ws, size_t ws_bytes,
                                 void* stream);
+
+/* The same call with the kernel chosen by number, for measurement: ev_begin / ev_end (hipEvent_t
+ * as void*, created by the caller with timing enabled, or NULL) are recorded on `stream`
+ * immediately before the first and immediately after the last launch of the tile-product kernel
+ * (a call of at most 524288 tokens on a layer of fewer than 1024 tiles is one launch: then the two
+ * events bracket that kernel alone, without the pre-pass before it and the reduction after it).
+ * Return codes as above with every argument number one higher (-1: unknown kernel). */
+#define BPDQ_HESSIAN_F16X2 0
+#define BPDQ_HESSIAN_BF16X3 1
+#define BPDQ_HESSIAN_F32 2
+int bpdq_hessian_accumulate_timed(int kernel, const float* Xc, int n_tok, int d_in, int ldx,
+                                  float scale, float* H, int symmetrize, void* ws, size_t ws_bytes,
+                                  void* stream, void* ev_begin, void* ev_end);
 
 /* ---- step 2: damping and U = chol(H^-1) (Sec. 3.1, "Quantization Error Compensation") ---
  * Reads the upper triangle of H.  Channels with H_ii == 0 are marked dead[i] = 1 and get
@@ -207,6 +231,24 @@ int bpdq_gather_columns(const float* W, int d_out, int d_in, const int* perm, fl
 int bpdq_scatter_columns(const float* Wp, int d_out, int d_in, const int* perm, float* W,
                          void* stream);
 int bpdq_gather_symmetric(const float* H, int d_in, const int* perm, float* Hp, void* stream);
+
+/* ---- measurement probes (not part of the method) ---------------------------------------------
+ * Ceilings of the GPU the library runs on, for quoting a kernel against what the hardware
+ * sustains as well as against its published peak.
+ * bpdq_probe_mfma: a register-only loop of one matrix-core instruction, no memory traffic:
+ *   kind 0 v_mfma_f32_32x32x2_f32, 1 v_mfma_f32_32x32x16_bf16, 2 v_mfma_f32_32x32x16_f16,
+ *   3 v_mfma_f64_16x16x4_f64;  data 0 zeros, 1 ones, 2 standard normal operand values (the
+ *   sustained clock depends on the operand bits that toggle);  waves_per_simd 1 or 2;
+ *   `groups` work-groups (256 = one per compute unit) of 4 * waves_per_simd wavefronts, each
+ *   issuing 8 * iters instructions on a 2 x 4 grid of independent accumulator tiles (fp64: 16 * iters
+ *   on 4 x 4).
+ *   out: device floats, groups * 256 * waves_per_simd of them (keeps the results alive).
+ *   flops (host, may be NULL): receives the flops the launch performs.  Time it with events.
+ * bpdq_probe_copy: dst[i] = src[i], n_floats (multiple of 4) floats, 16-byte aligned: the plain
+ *   streaming copy HBM counters and bandwidth are scaled by. */
+int bpdq_probe_mfma(int kind, int data, int waves_per_simd, int groups, int iters, float* out,
+                    double* flops /* host */, void* stream);
+int bpdq_probe_copy(const float* src, float* dst, long n_floats, void* stream);
 
 #ifdef __cplusplus
 }

@@ -18,12 +18,14 @@ _lib = None
 EXPORTS = [
     "bpdq_version",
     "bpdq_hessian_workspace_bytes", "bpdq_hessian_accumulate_f32", "bpdq_hessian_accumulate",
+    "bpdq_hessian_accumulate_bf16x3", "bpdq_hessian_accumulate_timed",
     "bpdq_prepare_workspace_bytes", "bpdq_prepare",
     "bpdq_quantize_workspace_bytes", "bpdq_quantize_layer", "bpdq_quantize_layers",
     "bpdq_pack_planes", "bpdq_dequant", "bpdq_coefs_to_fp16", "bpdq_dequant_fp16",
     "bpdq_channel_order_workspace_bytes", "bpdq_channel_order", "bpdq_channel_order_noalloc",
     "bpdq_gather_columns",
     "bpdq_scatter_columns", "bpdq_gather_symmetric", "bpdq_gemv",
+    "bpdq_probe_mfma", "bpdq_probe_copy",
 ]
 
 
@@ -54,8 +56,11 @@ def load():
     lib.bpdq_hessian_workspace_bytes.argtypes = [ci, ci]
     lib.bpdq_hessian_accumulate_f32.restype = ci
     lib.bpdq_hessian_accumulate_f32.argtypes = [vp, ci, ci, ci, cf, vp, ci, vp, sz, vp]
-    lib.bpdq_hessian_accumulate.restype = ci
-    lib.bpdq_hessian_accumulate.argtypes = [vp, ci, ci, ci, cf, vp, ci, vp, sz, vp]
+    for name in ("bpdq_hessian_accumulate", "bpdq_hessian_accumulate_bf16x3"):
+        getattr(lib, name).restype = ci
+        getattr(lib, name).argtypes = [vp, ci, ci, ci, cf, vp, ci, vp, sz, vp]
+    lib.bpdq_hessian_accumulate_timed.restype = ci
+    lib.bpdq_hessian_accumulate_timed.argtypes = [ci, vp, ci, ci, ci, cf, vp, ci, vp, sz, vp, vp, vp]
     lib.bpdq_prepare_workspace_bytes.restype = sz
     lib.bpdq_prepare_workspace_bytes.argtypes = [ci]
     lib.bpdq_prepare.restype = ci
@@ -89,6 +94,10 @@ def load():
     lib.bpdq_scatter_columns.argtypes = [vp, ci, ci, vp, vp, vp]
     lib.bpdq_gather_symmetric.restype = ci
     lib.bpdq_gather_symmetric.argtypes = [vp, ci, vp, vp, vp]
+    lib.bpdq_probe_mfma.restype = ci
+    lib.bpdq_probe_mfma.argtypes = [ci, ci, ci, ci, ci, vp, ctypes.POINTER(ctypes.c_double), vp]
+    lib.bpdq_probe_copy.restype = ci
+    lib.bpdq_probe_copy.argtypes = [vp, vp, ctypes.c_long, vp]
     _lib = lib
     return lib
 
@@ -124,8 +133,8 @@ def bpdq_hessian_workspace_bytes(n_tok: int, d_in: int) -> int:
 
 
 def bpdq_hessian_accumulate(Xc, H, scale=2.0, symmetrize=False, ws=None, _entry="bpdq_hessian_accumulate"):
-    """H += scale * Xc^T Xc (upper triangle; mirrored when symmetrize), on the bf16 matrix cores
-    with three exact bf16 pieces per value (fp32 accuracy)."""
+    """H += scale * Xc^T Xc (upper triangle; mirrored when symmetrize), on the fp16 matrix cores
+    with two fp16 halves per channel-scaled value."""
     lib = load()
     _dev(H, torch.float32, "H")
     if not (Xc.is_cuda and Xc.dtype == torch.float32 and Xc.dim() == 2 and Xc.stride(1) == 1):
@@ -146,6 +155,32 @@ def bpdq_hessian_accumulate(Xc, H, scale=2.0, symmetrize=False, ws=None, _entry=
 def bpdq_hessian_accumulate_f32(Xc, H, scale=2.0, symmetrize=False, ws=None):
     """bpdq_hessian_accumulate on the fp32 matrix cores."""
     return bpdq_hessian_accumulate(Xc, H, scale, symmetrize, ws, _entry="bpdq_hessian_accumulate_f32")
+
+
+def bpdq_hessian_accumulate_bf16x3(Xc, H, scale=2.0, symmetrize=False, ws=None):
+    """bpdq_hessian_accumulate on the bf16 matrix cores, three bf16 pieces per value."""
+    return bpdq_hessian_accumulate(Xc, H, scale, symmetrize, ws, _entry="bpdq_hessian_accumulate_bf16x3")
+
+
+HESSIAN_KERNELS = {"f16x2": 0, "bf16x3": 1, "f32": 2}
+
+
+def bpdq_hessian_accumulate_timed(kernel, Xc, H, scale=2.0, symmetrize=False, ws=None, ev_begin=None,
+                                  ev_end=None):
+    """bpdq_hessian_accumulate with the kernel chosen by name; ev_begin / ev_end are torch.cuda.Event
+    objects (timing enabled, recorded at least once before so that they exist) that the library
+    records right around the tile-product kernel."""
+    lib = load()
+    _dev(H, torch.float32, "H")
+    n_tok, d_in = Xc.shape
+    if ws is None:
+        ws = _workspace(lib.bpdq_hessian_workspace_bytes(n_tok, d_in), H.device)
+    ev = [ctypes.c_void_p(0 if e is None else e.cuda_event) for e in (ev_begin, ev_end)]
+    rc = lib.bpdq_hessian_accumulate_timed(HESSIAN_KERNELS[kernel], _ptr(Xc), n_tok, d_in,
+                                           Xc.stride(0) if n_tok > 1 else d_in, scale, _ptr(H),
+                                           int(bool(symmetrize)), _ptr(ws), ws.numel(), _stream(), ev[0], ev[1])
+    _check(rc, "bpdq_hessian_accumulate_timed")
+    return H
 
 
 def bpdq_prepare_workspace_bytes(d_in: int) -> int:
@@ -358,3 +393,28 @@ def bpdq_gemv(planes, coefs_h, group, x, y=None):
     _check(lib.bpdq_gemv(_ptr(planes), _ptr(coefs_h), d_out, d_in, bits, group, _ptr(x), _ptr(y),
                          _stream()), "bpdq_gemv")
     return y
+
+
+PROBE_KINDS = {"f32": 0, "bf16": 1, "f16": 2, "f64": 3}
+PROBE_DATA = {"zeros": 0, "ones": 1, "normal": 2}
+
+
+def bpdq_probe_mfma(kind, data, waves_per_simd, groups, iters, out):
+    """Enqueue one register-only matrix-core loop; returns the flops it performs."""
+    lib = load()
+    _dev(out, torch.float32, "out")
+    if out.numel() < groups * 256 * waves_per_simd:
+        raise BpdqError("out: too small")
+    flops = ctypes.c_double(0.0)
+    _check(lib.bpdq_probe_mfma(PROBE_KINDS[kind], PROBE_DATA[data], waves_per_simd, groups, iters,
+                               _ptr(out), ctypes.byref(flops), _stream()), "bpdq_probe_mfma")
+    return flops.value
+
+
+def bpdq_probe_copy(src, dst):
+    lib = load()
+    _dev(src, torch.float32, "src")
+    _dev(dst, torch.float32, "dst")
+    _check(lib.bpdq_probe_copy(_ptr(src), _ptr(dst), min(src.numel(), dst.numel()), _stream()),
+           "bpdq_probe_copy")
+    return dst

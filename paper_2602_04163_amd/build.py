@@ -15,7 +15,7 @@ LIB = os.path.join(HERE, "libbpdq.so")
 SOURCES = ["group_sweep_k3_g256.hip",
            "group_sweep_k3_g256u.hip", "group_sweep_k2_g256.hip", "group_sweep_k2_g256u.hip",
            "group_sweep_k1_g256.hip", "group_sweep_k1_g256u.hip", "group_sweep_k4.hip",
-           "group_sweep_k3.hip", "group_sweep_k2.hip", "group_sweep_k1.hip", "hessian.hip", "prepare.hip", "quantize.hip", "order.hip", "gemv.hip"]
+           "group_sweep_k3.hip", "group_sweep_k2.hip", "group_sweep_k1.hip", "hessian.hip", "prepare.hip", "quantize.hip", "order.hip", "gemv.hip", "ceilings.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -1,8 +1,10 @@
 // Step 1 of the pass: calibration Hessian H += scale * Xc^T Xc (paper Sec. 3.1, H = X X^T).
 //
-// A symmetric rank-k update on the matrix cores, in two kernels that share everything but the
-// tile product: fp32 MFMAs (bpdq_hessian_accumulate_f32), or bf16 MFMAs on three exact bf16 pieces
-// of every value (bpdq_hessian_accumulate; mfma_split_bf16.h).  Only the upper triangle
+// A symmetric rank-k update on the matrix cores, in three kernels that share everything but the
+// tile product: fp32 MFMAs (bpdq_hessian_accumulate_f32), bf16 MFMAs on three exact bf16 pieces
+// of every value (bpdq_hessian_accumulate_bf16x3; mfma_split_bf16.h), or fp16 MFMAs on two fp16
+// halves of every value, split and laid out in operand order by a streaming pre-pass
+// (bpdq_hessian_accumulate; mfma_split_f16.h).  Only the upper triangle
 // of 256 x 256 tiles is computed, and of a diagonal tile only the 32 x 32 blocks on or above the diagonal.
 // The token axis is cut into deterministic slices so that the work-groups fill the 256 compute
 // units in whole rounds: off-diagonal tiles into S_off slices, diagonal tiles (5/8 of the work
@@ -11,6 +13,7 @@
 // bit-reproducible).
 #include "mfma_kmajor.h"
 #include "mfma_split_bf16.h"
+#include "mfma_split_f16.h"
 
 namespace bpdq {
 
@@ -53,15 +56,18 @@ static double hess_makespan(int n_full, double c_full, int n_short, double c_sho
 // 52 k tokens and -2.5e-6 after 8 k tokens on the split path.  Both paths therefore end every
 // chain after kChainTokens[kind] tokens; the partial sums are added by ordinary round-to-nearest
 // fp32 additions, which do not drift.
-constexpr int kChainTokens[2] = {16384, 8192};
+constexpr int kChainTokens[3] = {16384, 8192, 8192};
 constexpr int kMaxSlices = 64;
 
-// kind 0: fp32 MFMA kernel; kind 1: split-bf16 kernel (about 1.8 times the rate per token)
+// kind 0: fp32 MFMA kernel; kind 1: split-bf16 kernel (about 1.8 times the rate per token);
+// kind 2: pre-split fp16 kernel (about twice the rate of kind 1)
+enum : int { kKindF32 = 0, kKindBf16x3 = 1, kKindF16x2 = 2, kNumKinds = 3 };
+
 static HessPlan plan_hessian(int n_tok, int d_in, int kind) {
   // the last plan of each kind, per host thread (the search below costs a fraction of a millisecond,
   // which a stream of short calls would otherwise pay every time)
-  thread_local HessPlan cache[2];
-  thread_local int cache_n[2] = {-1, -1}, cache_d[2] = {-1, -1};
+  thread_local HessPlan cache[kNumKinds];
+  thread_local int cache_n[kNumKinds] = {-1, -1, -1}, cache_d[kNumKinds] = {-1, -1, -1};
   if (n_tok == cache_n[kind] && d_in == cache_d[kind]) return cache[kind];
   HessPlan p;
   p.nb = bpdq_ceil_div(d_in, HessGemm::kTileM);
@@ -72,8 +78,10 @@ static HessPlan plan_hessian(int n_tok, int d_in, int kind) {
   p.direct = true;
   if (n_tok > 0 && p.n_off + p.n_diag < 4 * kNumCU) {
     // per-token MFMA time of one 256 x 256 tile, fixed cost per work-group, cost per partial tile
-    const double us_per_tok = kind ? 0.14 : 0.26, us_fixed = 8.0, us_per_partial = 0.131;
-    const double diag_frac = 0.64;
+    constexpr double kUsPerTok[kNumKinds] = {0.26, 0.14, 0.055};
+    constexpr double kDiagFrac[kNumKinds] = {0.64, 0.64, 0.60};
+    const double us_per_tok = kUsPerTok[kind], us_fixed = 8.0, us_per_partial = 0.131;
+    const double diag_frac = kDiagFrac[kind];
     const int s_max = n_tok / 256 < kMaxSlices ? (n_tok / 256 < 1 ? 1 : n_tok / 256) : kMaxSlices;
     // every accumulation chain stays short (see kChainTokens)
     int s_min = bpdq_ceil_div(n_tok, kChainTokens[kind]);
@@ -191,6 +199,170 @@ __global__ __launch_bounds__(SplitSyrk::kThreads) void hess_syrk_bf16x3_kernel(
   hess_syrk_body<true>(X, n_tok, d, ldx, scale, H, partial, p);
 }
 
+// ---- pre-pass of the fp16 path ---------------------------------------------------------------
+// (1) per-channel largest magnitude of the call's tokens, as partial maxima over token ranges;
+// (2) per channel the power of two that brings that maximum into [2^13, 2^14) (so every half is
+//     far from the ends of the fp16 range whatever the activations' units), and its inverse;
+// (3) the split itself: X -> planes[piece][token / 8][channel] (see mfma_split_f16.h), zeros for
+//     the tokens up to the next multiple of 32 and the channels up to the next multiple of 256.
+constexpr int kColmaxRows = 1024;      // tokens per partial maximum
+constexpr int kSplitKgPerWG = 16;      // k-groups (8 tokens each) per work-group of the split
+
+__global__ __launch_bounds__(256) void hess_colmax_kernel(const float* __restrict__ X, int n_tok, int d,
+                                                          long ldx, float* __restrict__ pmax, int d_pad) {
+  __shared__ float4 red[4][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c = blockIdx.x * 256 + lane * 4;
+  const int t0 = blockIdx.y * kColmaxRows;
+  const int t1 = min(n_tok, t0 + kColmaxRows);
+  float4 m = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (c < d) {                                    // d % 4 == 0: the float4 is inside the row
+    const float* p = X + c;
+    for (int t = t0 + wave; t < t1; t += 32) {    // 8 rows of this wavefront in flight
+      float4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int tt = min(t + 4 * u, t1 - 1);    // past the end: the last row again
+        v[u] = *reinterpret_cast<const float4*>(p + (long)tt * ldx);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        m.x = fmaxf(m.x, fabsf(v[u].x)); m.y = fmaxf(m.y, fabsf(v[u].y));
+        m.z = fmaxf(m.z, fabsf(v[u].z)); m.w = fmaxf(m.w, fabsf(v[u].w));
+      }
+    }
+  }
+  red[wave][lane] = m;
+  __syncthreads();
+  if (wave == 0) {
+#pragma unroll
+    for (int w = 1; w < 4; ++w) {
+      const float4 o = red[w][lane];
+      m.x = fmaxf(m.x, o.x); m.y = fmaxf(m.y, o.y); m.z = fmaxf(m.z, o.z); m.w = fmaxf(m.w, o.w);
+    }
+    *reinterpret_cast<float4*>(pmax + (long)blockIdx.y * d_pad + c) = m;     // c < d_pad always
+  }
+}
+
+__global__ __launch_bounds__(256) void hess_scale_kernel(const float* __restrict__ pmax, int n_split,
+                                                         int d_pad, float* __restrict__ mul,
+                                                         float* __restrict__ inv) {
+  // 64 channels per work-group, the partial maxima of a channel dealt to four threads
+  __shared__ float red[4][64];
+  const int c = blockIdx.x * 64 + (threadIdx.x & 63), q = threadIdx.x >> 6;
+  float m = 0.f;
+  for (int s = q; s < n_split; s += 4) m = fmaxf(m, pmax[(long)s * d_pad + c]);
+  red[q][threadIdx.x & 63] = m;
+  __syncthreads();
+  if (q) return;
+  m = fmaxf(fmaxf(red[0][threadIdx.x], red[1][threadIdx.x]), fmaxf(red[2][threadIdx.x], red[3][threadIdx.x]));
+  int e = 0;
+  if (m > 0.f && m < 3.0e38f) {
+    int ex;
+    (void)frexpf(m, &ex);           // m = f * 2^ex, f in [0.5, 1)
+    e = 14 - ex;                    // m * 2^e in [2^13, 2^14)
+    e = e > 100 ? 100 : (e < -100 ? -100 : e);
+  }
+  mul[c] = ldexpf(1.0f, e);
+  inv[c] = ldexpf(1.0f, -e);
+}
+
+__device__ __forceinline__ unsigned pack_halves(_Float16 a, _Float16 b) {
+  return (unsigned)__builtin_bit_cast(unsigned short, a) | ((unsigned)__builtin_bit_cast(unsigned short, b) << 16);
+}
+
+__global__ __launch_bounds__(256) void hess_split_f16_kernel(const float* __restrict__ X, int n_tok, int d,
+                                                             long ldx, const float* __restrict__ mul,
+                                                             uint4* __restrict__ planes, long n_kg,
+                                                             int d_pad) {
+  const int ch = blockIdx.x * 256 + threadIdx.x;
+  const bool live = ch < d;
+  const int chc = live ? ch : d - 1;
+  const float s = mul[chc];
+  const float* p = X + chc;
+  const long kg0 = (long)blockIdx.y * kSplitKgPerWG;
+  const int t_last = n_tok - 1;
+  for (int g = 0; g < kSplitKgPerWG; g += 2) {
+    const long kg = kg0 + g;
+    if (kg >= n_kg) break;
+    float x[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const long t = 8 * kg + i;
+      x[i] = p[(t < t_last ? t : (long)t_last) * ldx];
+    }
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      if (kg + half >= n_kg) break;
+      unsigned hw[4], lw[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        _Float16 h[2], l[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          const int i = 8 * half + 2 * q + e;
+          const bool in = live && (8 * kg + i) < n_tok;
+          const float xs = in ? x[i] * s : 0.f;
+          h[e] = (_Float16)xs;                       // round to nearest even
+          l[e] = (_Float16)(xs - (float)h[e]);       // exact difference, then rounded
+        }
+        hw[q] = pack_halves(h[0], h[1]);
+        lw[q] = pack_halves(l[0], l[1]);
+      }
+      planes[(kg + half) * d_pad + ch] = make_uint4(hw[0], hw[1], hw[2], hw[3]);
+      planes[(n_kg + kg + half) * d_pad + ch] = make_uint4(lw[0], lw[1], lw[2], lw[3]);
+    }
+  }
+}
+
+// The tile product of the fp16 path and its epilogue: every result is brought back to the
+// activations' own units by the two channel factors (powers of two: exact).
+__global__ __launch_bounds__(SplitF16::kThreads, 1) void hess_syrk_f16x2_kernel(
+    const uint4* __restrict__ planes, long n_kg, int d_pad, const float* __restrict__ inv, int n_tok,
+    int d, float scale, float* __restrict__ H, float* __restrict__ partial, HessPlan p) {
+  const int n_off_items = p.n_off * p.S_off;
+  const int item = xcd_item(blockIdx.x, n_off_items, p);
+  int bi, bj, k_begin, k_end;
+  if (item < n_off_items) {
+    decode_off_tile(item % p.n_off, p.nb, bi, bj);
+    k_begin = (item / p.n_off) * p.k_off;
+    k_end = min(n_tok, k_begin + p.k_off);
+  } else {
+    const int j = item - n_off_items;
+    bi = bj = j % p.n_diag;
+    k_begin = (j / p.n_diag) * p.k_diag;
+    k_end = min(n_tok, k_begin + p.k_diag);
+  }
+  // two stages of 16 tokens per loop iteration; the planes are zero beyond n_tok
+  const int n_stage = k_end > k_begin ? 2 * ((k_end - k_begin + 2 * SplitF16::kStageK - 1) / (2 * SplitF16::kStageK)) : 0;
+  SplitF16::Acc acc;
+  SplitF16::zero(acc);
+  const int r0 = bi * SplitF16::kTile, c0 = bj * SplitF16::kTile;
+  if (bi == bj) SplitF16::run<true>(planes, n_kg, d_pad, r0, c0, k_begin / 8, n_stage, acc);
+  else SplitF16::run<false>(planes, n_kg, d_pad, r0, c0, k_begin / 8, n_stage, acc);
+  // the LDS ring is free now: the channel factors of this tile's rows and columns
+  extern __shared__ uint4 smem_f16[];
+  float* sInv = reinterpret_cast<float*>(smem_f16);
+  sInv[threadIdx.x] = inv[r0 + threadIdx.x];
+  sInv[256 + threadIdx.x] = inv[c0 + threadIdx.x];
+  __syncthreads();
+  if (p.direct) {
+    auto emit = [&](int row, int col, float v) {
+      const int r = r0 + row, c = c0 + col;
+      if (r < d && c < d) H[(long)r * d + c] += scale * (v * sInv[row] * sInv[256 + col]);
+    };
+    if (bi == bj) SplitF16::for_each_diag(acc, emit);
+    else SplitF16::for_each(acc, emit);
+  } else {
+    float* out = partial + (long)item * kTileFloats;
+    auto emit = [&](int row, int col, float v) {
+      out[row * SplitF16::kTile + col] = v * sInv[row] * sInv[256 + col];
+    };
+    if (bi == bj) SplitF16::for_each_diag(acc, emit);
+    else SplitF16::for_each(acc, emit);
+  }
+}
+
 // H[tile] += scale * sum_s partial[s][tile], slices added in index order.  64 work-groups per
 // tile; tiles 0 .. n_off-1 are off-diagonal, the rest diagonal.
 __global__ __launch_bounds__(256) void hess_reduce_kernel(const float* __restrict__ partial,
@@ -259,42 +431,103 @@ static int hessian_launch_tokens(int kind, int n_left, int d_in) {
   return n;
 }
 
+// Workspace of one launch of n_part tokens: split-K partial tiles, then (fp16 path) the split
+// planes, the partial channel maxima and the two channel factors.
+struct HessWs {
+  size_t partial_off, planes_off, pmax_off, mul_off, inv_off, total;
+  long n_kg;
+  int d_pad, n_split;
+};
+
+static HessWs hessian_ws_layout(int kind, int n_part, int d_in) {
+  HessWs L{};
+  size_t off = 0;
+  L.partial_off = off;
+  off += bpdq_align_up(plan_hessian(n_part, d_in, kind).ws_bytes(), 256);
+  if (kind == kKindF16x2) {
+    L.d_pad = (int)bpdq_align_up((size_t)d_in, SplitF16::kTile);
+    L.n_kg = (long)bpdq_align_up((size_t)n_part, 2 * SplitF16::kStageK) / 8;
+    L.n_split = bpdq_ceil_div(n_part, kColmaxRows);
+    L.planes_off = off; off += bpdq_align_up((size_t)2 * L.n_kg * L.d_pad * sizeof(uint4), 256);
+    L.pmax_off = off;   off += bpdq_align_up((size_t)L.n_split * L.d_pad * sizeof(float), 256);
+    L.mul_off = off;    off += bpdq_align_up((size_t)L.d_pad * sizeof(float), 256);
+    L.inv_off = off;    off += bpdq_align_up((size_t)L.d_pad * sizeof(float), 256);
+  }
+  L.total = off;
+  return L;
+}
+
 // the first launch of a call is its largest
 static size_t hessian_ws_bytes(int kind, int n_tok, int d_in) {
-  return plan_hessian(hessian_launch_tokens(kind, n_tok, d_in), d_in, kind).ws_bytes();
+  return hessian_ws_layout(kind, hessian_launch_tokens(kind, n_tok, d_in), d_in).total;
 }
 
 static int hessian_accumulate(int kind, const float* Xc, int n_tok, int d_in, int ldx, float scale,
-                              float* H, int symmetrize, void* ws, size_t ws_bytes, void* stream_) {
+                              float* H, int symmetrize, void* ws, size_t ws_bytes, void* stream_,
+                              void* ev_begin = nullptr, void* ev_end = nullptr) {
   hipStream_t stream = static_cast<hipStream_t>(stream_);
+  if (kind < 0 || kind >= kNumKinds) return -11;
   if (n_tok < 0) return -2;
   if (d_in <= 0 || d_in % 4) return -3;
   if (ldx < d_in || ldx % 4) return -4;
   if (n_tok > 0 && (!Xc || (reinterpret_cast<uintptr_t>(Xc) & 15))) return -1;
   if (!H || (reinterpret_cast<uintptr_t>(H) & 15)) return -6;
   const size_t need = n_tok > 0 ? hessian_ws_bytes(kind, n_tok, d_in) : 0;
-  if (need > 0 && (!ws || (reinterpret_cast<uintptr_t>(ws) & 15))) return -8;
+  if (need > 0 && (!ws || (reinterpret_cast<uintptr_t>(ws) & 255))) return -8;
   if (ws_bytes < need) return -9;
+  char* base = static_cast<char*>(ws);
   for (int done = 0; done < n_tok;) {
     const int n_part = hessian_launch_tokens(kind, n_tok - done, d_in);
     const HessPlan p = plan_hessian(n_part, d_in, kind);
+    const HessWs L = hessian_ws_layout(kind, n_part, d_in);
+    float* partial = reinterpret_cast<float*>(base + L.partial_off);
     const float* Xpart = Xc + (long)done * ldx;
+    const bool first = (done == 0);
     done += n_part;
-    BPDQ_HIP_TRY(bpdq_lds_limit<&hess_syrk_f32_kernel>(HessGemm::kLdsBytes));
-    BPDQ_HIP_TRY(bpdq_lds_limit<&hess_syrk_bf16x3_kernel>(SplitSyrk::kLdsBytes));
-    if (kind == 0) {
+    // (the pre-pass of the fp16 path precedes the first event; later launches' pre-passes fall
+    // between the two events)
+    auto mark_begin = [&]() -> int {
+      if (first && ev_begin) BPDQ_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(ev_begin), stream));
+      return 0;
+    };
+    if (kind == kKindF32) {
+      if (mark_begin()) return BPDQ_ERR_LAUNCH;
+      BPDQ_HIP_TRY(bpdq_lds_limit<&hess_syrk_f32_kernel>(HessGemm::kLdsBytes));
       hipLaunchKernelGGL(hess_syrk_f32_kernel, dim3(p.items()), dim3(HessGemm::kThreads),
                          HessGemm::kLdsBytes, stream, Xpart, n_part, d_in, (long)ldx, scale, H,
-                         static_cast<float*>(ws), p);
-    } else {
+                         partial, p);
+    } else if (kind == kKindBf16x3) {
+      if (mark_begin()) return BPDQ_ERR_LAUNCH;
+      BPDQ_HIP_TRY(bpdq_lds_limit<&hess_syrk_bf16x3_kernel>(SplitSyrk::kLdsBytes));
       hipLaunchKernelGGL(hess_syrk_bf16x3_kernel, dim3(p.items()), dim3(SplitSyrk::kThreads),
                          SplitSyrk::kLdsBytes, stream, Xpart, n_part, d_in, (long)ldx, scale, H,
-                         static_cast<float*>(ws), p);
+                         partial, p);
+    } else {
+      BPDQ_HIP_TRY(bpdq_lds_limit<&hess_syrk_f16x2_kernel>(SplitF16::kLdsBytes));
+      uint4* planes = reinterpret_cast<uint4*>(base + L.planes_off);
+      float* pmax = reinterpret_cast<float*>(base + L.pmax_off);
+      float* mul = reinterpret_cast<float*>(base + L.mul_off);
+      float* inv = reinterpret_cast<float*>(base + L.inv_off);
+      const int cb = L.d_pad / SplitF16::kTile;
+      hipLaunchKernelGGL(hess_colmax_kernel, dim3(cb, L.n_split), dim3(256), 0, stream, Xpart, n_part,
+                         d_in, (long)ldx, pmax, L.d_pad);
+      BPDQ_LAUNCH_CHECK();
+      hipLaunchKernelGGL(hess_scale_kernel, dim3(L.d_pad / 64), dim3(256), 0, stream, pmax, L.n_split,
+                         L.d_pad, mul, inv);
+      BPDQ_LAUNCH_CHECK();
+      hipLaunchKernelGGL(hess_split_f16_kernel, dim3(cb, (unsigned)bpdq_ceil_div((int)L.n_kg, kSplitKgPerWG)),
+                         dim3(256), 0, stream, Xpart, n_part, d_in, (long)ldx, mul, planes, L.n_kg, L.d_pad);
+      BPDQ_LAUNCH_CHECK();
+      if (mark_begin()) return BPDQ_ERR_LAUNCH;
+      hipLaunchKernelGGL(hess_syrk_f16x2_kernel, dim3(p.items()), dim3(SplitF16::kThreads),
+                         SplitF16::kLdsBytes, stream, planes, L.n_kg, L.d_pad, inv, n_part, d_in, scale,
+                         H, partial, p);
     }
     BPDQ_LAUNCH_CHECK();
+    if (done >= n_tok && ev_end) BPDQ_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(ev_end), stream));
     if (!p.direct) {
       hipLaunchKernelGGL(hess_reduce_kernel, dim3((p.n_off + p.n_diag) * 64), dim3(256), 0, stream,
-                         static_cast<const float*>(ws), p, d_in, scale, H);
+                         partial, p, d_in, scale, H);
       BPDQ_LAUNCH_CHECK();
     }
   }
@@ -308,19 +541,42 @@ static int hessian_accumulate(int kind, const float* Xc, int n_tok, int d_in, in
 
 extern "C" size_t bpdq_hessian_workspace_bytes(int n_tok, int d_in) {
   if (n_tok <= 0 || d_in <= 0) return 0;
-  // one workspace serves either kernel
-  const size_t a = hessian_ws_bytes(0, n_tok, d_in), b = hessian_ws_bytes(1, n_tok, d_in);
-  return a > b ? a : b;
+  // one workspace serves any of the kernels
+  size_t need = 0;
+  for (int kind = 0; kind < kNumKinds; ++kind) {
+    const size_t b = hessian_ws_bytes(kind, n_tok, d_in);
+    need = b > need ? b : need;
+  }
+  return need;
 }
 
 extern "C" int bpdq_hessian_accumulate_f32(const float* Xc, int n_tok, int d_in, int ldx, float scale,
-                                       float* H, int symmetrize, void* ws, size_t ws_bytes,
-                                       void* stream) {
-  return hessian_accumulate(0, Xc, n_tok, d_in, ldx, scale, H, symmetrize, ws, ws_bytes, stream);
+                                           float* H, int symmetrize, void* ws, size_t ws_bytes,
+                                           void* stream) {
+  return hessian_accumulate(kKindF32, Xc, n_tok, d_in, ldx, scale, H, symmetrize, ws, ws_bytes, stream);
 }
 
-extern "C" int bpdq_hessian_accumulate(const float* Xc, int n_tok, int d_in, int ldx,
-                                              float scale, float* H, int symmetrize, void* ws,
-                                              size_t ws_bytes, void* stream) {
-  return hessian_accumulate(1, Xc, n_tok, d_in, ldx, scale, H, symmetrize, ws, ws_bytes, stream);
+extern "C" int bpdq_hessian_accumulate_bf16x3(const float* Xc, int n_tok, int d_in, int ldx, float scale,
+                                              float* H, int symmetrize, void* ws, size_t ws_bytes,
+                                              void* stream) {
+  return hessian_accumulate(kKindBf16x3, Xc, n_tok, d_in, ldx, scale, H, symmetrize, ws, ws_bytes, stream);
+}
+
+extern "C" int bpdq_hessian_accumulate_timed(int kernel, const float* Xc, int n_tok, int d_in, int ldx,
+                                             float scale, float* H, int symmetrize, void* ws,
+                                             size_t ws_bytes, void* stream, void* ev_begin, void* ev_end) {
+  const int kind = kernel == BPDQ_HESSIAN_F16X2 ? kKindF16x2
+                   : kernel == BPDQ_HESSIAN_BF16X3 ? kKindBf16x3
+                   : kernel == BPDQ_HESSIAN_F32 ? kKindF32 : -1;
+  if (kind < 0) return -1;
+  const int rc = hessian_accumulate(kind, Xc, n_tok, d_in, ldx, scale, H, symmetrize, ws, ws_bytes, stream,
+                                    ev_begin, ev_end);
+  return rc < 0 && rc > -11 ? rc - 1 : rc;      // the arguments are shifted by one
+}
+
+// the default entry: two fp16 halves per scaled value
+extern "C" int bpdq_hessian_accumulate(const float* Xc, int n_tok, int d_in, int ldx, float scale,
+                                       float* H, int symmetrize, void* ws, size_t ws_bytes,
+                                       void* stream) {
+  return hessian_accumulate(kKindF16x2, Xc, n_tok, d_in, ldx, scale, H, symmetrize, ws, ws_bytes, stream);
 }

@@ -149,13 +149,17 @@ def _end_to_end(dev, wl, tokens_per_call=0, hess=None, fp64_decisions=False, tea
     return dict(h_err=h_err, plane_frac=plane_frac, obj_gpu=o_g, obj_oracle=o_r)
 
 
-@pytest.mark.parametrize("hess", ["bf16x3", "f32"])
+HESSIANS = {"f16x2": bq.bpdq_hessian_accumulate, "bf16x3": bq.bpdq_hessian_accumulate_bf16x3,
+            "f32": bq.bpdq_hessian_accumulate_f32}
+
+
+@pytest.mark.parametrize("hess", ["f16x2", "bf16x3", "f32"])
 def test_benchmark_workload_full_size(dev, hess):
     """configs[1]: 3584 x 3584, 262144 tokens, 2-bit, g = B = 128, 5 iterations; one Hessian
     call over all tokens, exactly as bench.py launches it (bench.py times bpdq_hessian_accumulate,
-    the bf16x3 kernel; bpdq_hessian_accumulate_f32 is the alternative)."""
-    fn = {"f32": bq.bpdq_hessian_accumulate_f32, "bf16x3": bq.bpdq_hessian_accumulate}[hess]
-    first = hess == "bf16x3"
+    the fp16-halves kernel; the bf16-pieces and fp32 matrix-core entries are the alternatives)."""
+    fn = HESSIANS[hess]
+    first = hess == "f16x2"
     _end_to_end(dev, wk.WORKLOADS["cfg2_qwen7b_attn"], hess=fn, fp64_decisions=first, teacher=first)
 
 
@@ -163,8 +167,8 @@ def test_benchmark_workload_chunked_hessian(dev):
     """Same layer shape with the Hessian streamed in 4096-token calls (fewer tokens so the
     oracle stays short)."""
     wl = wk.WORKLOADS["cfg2_qwen7b_attn"].scaled(n_tok=16384)
-    _end_to_end(dev, wl, tokens_per_call=4096)
-    _end_to_end(dev, wl, tokens_per_call=4096, hess=bq.bpdq_hessian_accumulate_f32)
+    for fn in HESSIANS.values():
+        _end_to_end(dev, wl, tokens_per_call=4096, hess=fn)
 
 
 SCALED = {
