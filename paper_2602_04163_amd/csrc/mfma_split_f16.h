@@ -38,7 +38,10 @@ struct SplitF16 {
   static constexpr int kVecRun = kTile;                    // one (piece, k-group) run: 256 vectors = 4 KB
   static constexpr int kVecOperand = 4 * kVecRun;          // [piece 2][k-group 2][channel 256]
   static constexpr int kVecStage = 2 * kVecOperand;        // operands A, B: 32 KB
-  static constexpr int kStages = 4;
+#ifndef BPDQ_F16_STAGES
+#define BPDQ_F16_STAGES 4
+#endif
+  static constexpr int kStages = BPDQ_F16_STAGES;
   static constexpr size_t kLdsBytes = (size_t)kStages * kVecStage * 16u;
   static constexpr int kDiagBlocks = 9;                    // blocks per wavefront of a diagonal tile
 
@@ -95,46 +98,34 @@ struct SplitF16 {
     if constexpr (T == 2) c = __builtin_amdgcn_mfma_f32_32x32x16_f16(a.h, b.h, c, 0, 0, 0);
   }
 
-  // Fragments of one stage for this wavefront.  Off-diagonal: f[0..3] the four row blocks of A,
-  // f[4..7] the four column blocks of B.  Diagonal: f[b] = block b of the one operand.
-  template <bool DIAG>
-  __device__ static __forceinline__ void read_stage(const uint4* smem, int buf, int a_idx, int b_idx,
-                                                    Frag (&f)[8]) {
+  // Fragment t (0..7) of a stage for this wavefront.  Off-diagonal: 0..3 the four row blocks of A,
+  // 4..7 the four column blocks of B.  Diagonal: block t of the one operand.
+  template <bool DIAG, int T>
+  __device__ static __forceinline__ Frag read_one(const uint4* smem, int buf, int a_idx, int b_idx) {
     const int base = buf * kVecStage;
-    if constexpr (DIAG) {
-#pragma unroll
-      for (int b = 0; b < 8; ++b) f[b] = read_frag(smem, base + a_idx + 32 * b);
-    } else {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) f[i] = read_frag(smem, base + a_idx + 32 * i);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) f[4 + j] = read_frag(smem, base + kVecOperand + b_idx + 32 * j);
-    }
+    if constexpr (DIAG) return read_frag(smem, base + a_idx + 32 * T);
+    else if constexpr (T < 4) return read_frag(smem, base + a_idx + 32 * T);
+    else return read_frag(smem, base + kVecOperand + b_idx + 32 * (T - 4));
   }
 
-  template <int W>
-  __device__ static __forceinline__ void mfma_diag(const Frag (&f)[8], Acc& acc) {
-#pragma unroll
-    for (int q = 0; q < kDiagBlocks; ++q) piece_mfma<0>(f[kDiagRow[W][q]], f[kDiagCol[W][q]], acc.c[q / 4][q % 4]);
-#pragma unroll
-    for (int q = 0; q < kDiagBlocks; ++q) piece_mfma<1>(f[kDiagRow[W][q]], f[kDiagCol[W][q]], acc.c[q / 4][q % 4]);
-#pragma unroll
-    for (int q = 0; q < kDiagBlocks; ++q) piece_mfma<2>(f[kDiagRow[W][q]], f[kDiagCol[W][q]], acc.c[q / 4][q % 4]);
+  // The MFMAs of a stage in issue order: three passes (products l h', h l', h h': smallest first)
+  // over the wavefront's blocks, so that consecutive instructions write different accumulators.
+  // Off-diagonal: 16 blocks (i, j); diagonal: the 9 blocks of wavefront W's schedule.
+  template <bool DIAG, int W>
+  static constexpr int kMfmaPerStage = 3 * (DIAG ? kDiagBlocks : 16);
+  template <bool DIAG, int W, int N>
+  __device__ static __forceinline__ void mfma_n(const Frag (&f)[8], Acc& acc) {
+    constexpr int nb = DIAG ? kDiagBlocks : 16;
+    constexpr int t = N / nb, q = N % nb;
+    if constexpr (DIAG) piece_mfma<t>(f[kDiagRow[W][q]], f[kDiagCol[W][q]], acc.c[q / 4][q % 4]);
+    else piece_mfma<t>(f[q / 4], f[4 + q % 4], acc.c[q / 4][q % 4]);
   }
-  __device__ static __forceinline__ void mfma_full(const Frag (&f)[8], Acc& acc) {
-    // consecutive instructions write different accumulators: no dependent issue
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) piece_mfma<0>(f[i], f[4 + j], acc.c[i][j]);
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) piece_mfma<1>(f[i], f[4 + j], acc.c[i][j]);
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) piece_mfma<2>(f[i], f[4 + j], acc.c[i][j]);
+  template <bool DIAG, int W, int N0, int N1>
+  __device__ static __forceinline__ void mfma_range(const Frag (&f)[8], Acc& acc) {
+    if constexpr (N0 < N1) {
+      mfma_n<DIAG, W, N0>(f, acc);
+      mfma_range<DIAG, W, N0 + 1, N1>(f, acc);
+    }
   }
 
   // acc += sum over k-groups [kg_begin, kg_begin + 2 n_stage) of the tile product of the channel
@@ -198,21 +189,39 @@ struct SplitF16 {
     const int a_idx = (lane >> 5) * kVecRun + (DIAG ? 0 : wm * 128) + (lane & 31);
     const int b_idx = (lane >> 5) * kVecRun + wn * 128 + (lane & 31);
     Frag f0[8], f1[8];
-    read_stage<DIAG>(smem_f16, 0, a_idx, b_idx, f0);
+    f0[0] = read_one<DIAG, 0>(smem_f16, 0, a_idx, b_idx); f0[1] = read_one<DIAG, 1>(smem_f16, 0, a_idx, b_idx);
+    f0[2] = read_one<DIAG, 2>(smem_f16, 0, a_idx, b_idx); f0[3] = read_one<DIAG, 3>(smem_f16, 0, a_idx, b_idx);
+    f0[4] = read_one<DIAG, 4>(smem_f16, 0, a_idx, b_idx); f0[5] = read_one<DIAG, 5>(smem_f16, 0, a_idx, b_idx);
+    f0[6] = read_one<DIAG, 6>(smem_f16, 0, a_idx, b_idx); f0[7] = read_one<DIAG, 7>(smem_f16, 0, a_idx, b_idx);
 
+    // One stage = eight steps; step t requests run t of the stage kAhead ahead (runs 0..3 only on a
+    // diagonal tile), reads fragment t of the next stage and issues an eighth of this stage's
+    // MFMAs.  A wavefront is alone on its SIMD, so whatever it issues between two MFMAs must fit
+    // under the 32 cycles the matrix pipe spends on one: spread like this, the loads and LDS
+    // reads cost the pipe nothing, bunched at the head of the stage they would stall it.
+    constexpr int kM = kMfmaPerStage<DIAG, W>;
     auto stage = [&](int s, Frag (&cur)[8], Frag (&nxt)[8]) {
       // stage s + 1 must be complete in LDS before its fragments are read below; the barrier also
-      // tells that every wavefront has consumed stage s - 1, whose slot the next request overwrites
+      // tells that every wavefront has consumed stage s - 1, whose slot the requests overwrite
+      // (a bare barrier: the LDS reads still in flight belong to this stage's own slot, which no
+      // request touches, so they need not be waited for here; the empty statement keeps the
+      // compiler from moving an LDS access across the barrier)
       wait_vm<kRuns*(kAhead - 2)>();
-      __syncthreads();
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
       const int sr = s + kAhead;
-      request(sr < last ? sr : last, sr);
-      // (after the last stage this reads a slot whose contents nobody uses)
-      read_stage<DIAG>(smem_f16, (s + 1) % kStages, a_idx, b_idx, nxt);
+      const int sc = sr < last ? sr : last;
+      const unsigned slot = lds0 + (unsigned)(sr % kStages) * (kVecStage * 16u);
+      const int nb = (s + 1) % kStages;          // (after the last stage: a slot nobody uses)
+#define BPDQ_F16_STEP(T)                                                                         \
+      if constexpr (T < kRuns)                                                                     \
+        dma_1k(src[T < kRuns ? T : 0] + (long)sc * stage_stride, voff, slot + (unsigned)(T) * (kVecRun * 16u)); \
+      nxt[T] = read_one<DIAG, T>(smem_f16, nb, a_idx, b_idx);                                      \
+      mfma_range<DIAG, W, (T) * kM / 8, ((T) + 1) * kM / 8>(cur, acc);                             \
       __builtin_amdgcn_sched_barrier(0);
-      if constexpr (DIAG) mfma_diag<W>(cur, acc);
-      else mfma_full(cur, acc);
-      __builtin_amdgcn_sched_barrier(0);                   // the MFMAs stay in their own stage
+      BPDQ_F16_STEP(0) BPDQ_F16_STEP(1) BPDQ_F16_STEP(2) BPDQ_F16_STEP(3)
+      BPDQ_F16_STEP(4) BPDQ_F16_STEP(5) BPDQ_F16_STEP(6) BPDQ_F16_STEP(7)
+#undef BPDQ_F16_STEP
     };
     for (int s = 0; s < n_stage; s += 2) {
       stage(s, f0, f1);
