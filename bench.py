@@ -43,7 +43,44 @@ def parse():
     ap.add_argument("--ceilings", action="store_true",
                     help="measure the chip's own ceilings instead (register-only matrix-core loops, "
                          "streaming copy) and print them as one JSON line")
+    ap.add_argument("--block-update", action="store_true",
+                    help="measure the lazy block-update GEMM by itself (bpdq_block_update) at the five "
+                         "layer shapes and several depths K, and print one JSON line")
     return ap.parse_args()
+
+
+def block_update_probe():
+    """W'[:, K:] -= E_blk U[0:K, K:] for the first block of a layer of every workload shape: the
+    largest update of the layer, at the block depth the sweep uses (128) and at deeper ones."""
+    import torch
+    from paper_2602_04163_amd import binding as bq
+    bq.load()
+    dev = torch.device("cuda:0")
+    res = {"unit": "TFLOP/s", "fp32_mfma_peak": PEAK_MFMA_F32_TFLOPS, "hbm_peak_GBps": 8000.0, "cases": []}
+    for d_out, d_in in ((3584, 3584), (18944, 3584), (3584, 18944), (8192, 8192), (8192, 29568)):
+        lde = (d_out + 63) // 64 * 64
+        U = torch.randn((d_in, d_in), device=dev).triu_() * 0.05
+        Wp = torch.randn((d_out, d_in), device=dev) * 0.02
+        for Kd in (128, 256, 512, 1024):
+            Et = torch.randn((Kd, lde), device=dev) * 0.01
+            for _ in range(2):
+                bq.bpdq_block_update(Et, U, 0, Wp, Kd, d_in)
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(5)]
+            for a, b in ev:
+                a.record()
+                bq.bpdq_block_update(Et, U, 0, Wp, Kd, d_in)
+                b.record()
+            torch.cuda.synchronize()
+            ms = sorted(a.elapsed_time(b) for a, b in ev)[2]
+            flops = 2.0 * d_out * Kd * (d_in - Kd)
+            # compulsory traffic: the tail of W' read and written once, E_blk and the rows of U once
+            nbytes = 8.0 * d_out * (d_in - Kd) + 4.0 * Kd * (d_in - Kd) + 4.0 * Kd * d_out
+            res["cases"].append({"d_out": d_out, "d_in": d_in, "K": Kd, "us": round(ms * 1e3, 1),
+                                 "tflops": round(flops / ms / 1e9, 1),
+                                 "frac_of_fp32_mfma_peak": round(flops / ms / 1e9 / PEAK_MFMA_F32_TFLOPS, 3),
+                                 "GBps_compulsory": round(nbytes / ms / 1e6, 1)})
+        del U, Wp
+    print(json.dumps(res), flush=True)
 
 
 def ceilings():
@@ -142,6 +179,9 @@ def main():
         sys.exit(1)
     if args.ceilings:
         ceilings()
+        return
+    if args.block_update:
+        block_update_probe()
         return
     bq.load()
     dev = torch.device("cuda:0")

@@ -153,6 +153,18 @@ int bpdq_quantize_layer(const float* W, int d_out, int d_in, const float* U,
                         uint32_t* planes, float* coefs, float* W_hat, double* grp_err,
                         int* grp_iter, void* ws, size_t ws_bytes, void* stream);
 
+/* The lazy block update on its own (Eq. 4 applied to a whole block of finished columns, App. B.3
+ * tail form), as bpdq_quantize_layer applies it inside the sweep:
+ *     Wp[:, c_begin:c_end] -= E_blk U[k0:k0+Kd, c_begin:c_end]
+ * on the fp32 matrix cores, in place.
+ *   Et : the block's propagation coordinates, transposed: Kd x lde, row k holds E[:, k0 + k] for all
+ *        d_out rows (lde >= d_out; the lde - d_out padding entries of a row are read and ignored).
+ *   U  : the factor from bpdq_prepare, leading dimension ldu;  Wp: d_out x ldw working weights.
+ * Requirements: lde, ldu multiples of 4; Et, U 16-byte aligned; c_begin, c_end multiples of 4.
+ * Exposed for parity tests and for measuring this GEMM by itself. */
+int bpdq_block_update(const float* Et, int lde, int Kd, const float* U, int ldu, int k0, float* Wp,
+                      int ldw, int d_out, int c_begin, int c_end, void* stream);
+
 /* Layers that share one input (q/k/v, up/gate) share H and U; stacked by rows they go through the
  * sweep in one call.  Every formula of the method is row-wise; only the choice of the kept
  * iterate is made per weight matrix (Sec. 3.3), so it is made per layer here:

@@ -20,7 +20,7 @@ EXPORTS = [
     "bpdq_hessian_workspace_bytes", "bpdq_hessian_accumulate_f32", "bpdq_hessian_accumulate",
     "bpdq_hessian_accumulate_bf16x3", "bpdq_hessian_accumulate_timed",
     "bpdq_prepare_workspace_bytes", "bpdq_prepare",
-    "bpdq_quantize_workspace_bytes", "bpdq_quantize_layer", "bpdq_quantize_layers",
+    "bpdq_quantize_workspace_bytes", "bpdq_quantize_layer", "bpdq_quantize_layers", "bpdq_block_update",
     "bpdq_pack_planes", "bpdq_dequant", "bpdq_coefs_to_fp16", "bpdq_dequant_fp16",
     "bpdq_channel_order_workspace_bytes", "bpdq_channel_order", "bpdq_channel_order_noalloc",
     "bpdq_gather_columns",
@@ -72,6 +72,8 @@ def load():
     lib.bpdq_quantize_layers.restype = ci
     lib.bpdq_quantize_layers.argtypes = [vp, ci, ci, vp, vp, pp, ci, ctypes.POINTER(ci), vp, vp, vp,
                                          vp, vp, vp, sz, vp]
+    lib.bpdq_block_update.restype = ci
+    lib.bpdq_block_update.argtypes = [vp, ci, ci, vp, ci, ci, vp, ci, ci, ci, ci, vp]
     lib.bpdq_pack_planes.restype = ci
     lib.bpdq_pack_planes.argtypes = [vp, ci, ci, ci, vp, vp]
     lib.bpdq_dequant.restype = ci
@@ -275,6 +277,19 @@ def bpdq_quantize_layers(W, seg_end, U, dead, params: BpdqParams, want_w_hat=Tru
                                   _ptr(ws), ws.numel(), _stream())
     _check(rc, "bpdq_quantize_layers")
     return out
+
+
+def bpdq_block_update(Et, U, k0, Wp, c_begin, c_end, d_out=None):
+    """Wp[:, c_begin:c_end] -= Et^T U[k0:k0+Kd, c_begin:c_end] in place (Et: Kd x lde, K-major)."""
+    lib = load()
+    _dev(Et, torch.float32, "Et")
+    _dev(U, torch.float32, "U")
+    _dev(Wp, torch.float32, "Wp")
+    Kd, lde = Et.shape
+    d_out = Wp.shape[0] if d_out is None else d_out
+    _check(lib.bpdq_block_update(_ptr(Et), lde, Kd, _ptr(U), U.shape[1], k0, _ptr(Wp), Wp.shape[1], d_out,
+                                 c_begin, c_end, _stream()), "bpdq_block_update")
+    return Wp
 
 
 def bpdq_pack_planes(codes, bits):

@@ -230,6 +230,32 @@ extern "C" int bpdq_quantize_layers(const float* W, int d_out, int d_in, const f
   return rc == -13 ? -15 : rc;
 }
 
+extern "C" int bpdq_block_update(const float* Et, int lde, int Kd, const float* U, int ldu, int k0,
+                                 float* Wp, int ldw, int d_out, int c_begin, int c_end, void* stream_) {
+  if (!Et || (reinterpret_cast<uintptr_t>(Et) & 15)) return -1;
+  if (lde < d_out || lde % 4) return -2;
+  if (Kd <= 0) return -3;
+  if (!U || (reinterpret_cast<uintptr_t>(U) & 15)) return -4;
+  if (ldu < c_end || ldu % 4) return -5;
+  if (k0 < 0) return -6;
+  if (!Wp) return -7;
+  if (ldw < c_end) return -8;
+  if (d_out <= 0) return -9;
+  if (c_begin < 0 || c_begin % 4) return -10;
+  if (c_end < c_begin || c_end % 4) return -11;
+  if (c_end == c_begin) return 0;
+  TailArgs ta{};
+  ta.Et = Et;
+  ta.Kd = Kd;
+  ta.k0 = k0;
+  ta.Wp = Wp;
+  ta.c_begin = c_begin;
+  ta.c_end = c_end;
+  ta.tiles_n = bpdq_ceil_div(c_end - c_begin, TailGemm::kTileN);
+  const int n_tiles = bpdq_ceil_div(d_out, TailGemm::kTileM) * ta.tiles_n;
+  return launch_tail_update(static_cast<hipStream_t>(stream_), ta, U, ldu, lde, ldw, d_out, n_tiles);
+}
+
 extern "C" int bpdq_pack_planes(const unsigned char* codes, int d_out, int d_in, int bits,
                                 uint32_t* planes, void* stream_) {
   hipStream_t stream = static_cast<hipStream_t>(stream_);

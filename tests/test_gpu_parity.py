@@ -465,6 +465,31 @@ def test_identity_hessian_on_gpu(dev):
     assert abs(out["grp_err"].cpu().numpy().sum() - ref["objective"]) / ref["objective"] < OBJ_TOL
 
 
+# ------------------------------------------------------------------ step 4: lazy block update
+@pytest.mark.parametrize("d_out,lde,Kd,k0,c0,c1,d_in", [
+    (200, 256, 128, 128, 256, 1000, 1024),      # ragged rows and a ragged last column tile
+    (128, 128, 64, 0, 64, 192, 192),            # one tile, short K
+    (515, 576, 1024, 0, 1024, 1536, 1536),      # deep K (the far-tail form)
+    (64, 64, 128, 256, 384, 384, 512),          # empty column range: nothing to do
+])
+def test_block_update_matches_definition(dev, d_out, lde, Kd, k0, c0, c1, d_in):
+    """W'[:, c0:c1] -= E_blk U[blk, c0:c1] (Eq. 4 for a whole block; App. B.3 tail form) against
+    the same product in fp64; columns outside [c0, c1) must not change."""
+    print(f"block update {d_out}x[{c0},{c1}) K={Kd}", flush=True)
+    g = torch.Generator().manual_seed(d_out + Kd)
+    Et = torch.randn((Kd, lde), generator=g) * 0.01
+    U = torch.triu(torch.randn((d_in, d_in), generator=g)) * 0.1
+    Wp = torch.randn((d_out, d_in), generator=g) * 0.02
+    want = Wp.double().clone()
+    want[:, c0:c1] -= Et[:, :d_out].double().T @ U[k0:k0 + Kd, c0:c1].double()
+    got = bq.bpdq_block_update(Et.to(dev), U.to(dev), k0, Wp.to(dev), c0, c1).cpu().double()
+    bound = 4e-6 * (Et[:, :d_out].double().abs().T @ U[k0:k0 + Kd].double().abs()) + 2e-7 * Wp.double().abs()
+    assert bool(((got - want).abs() <= bound + 1e-12).all())
+    keep = torch.ones(d_in, dtype=torch.bool)
+    keep[c0:c1] = False
+    assert torch.equal(got[:, keep], Wp.double()[:, keep])
+
+
 # ------------------------------------------------------------------ whole pass, tiny config
 def test_whole_pass_tiny_config(dev):
     print("whole pass cfg1", flush=True)
