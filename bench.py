@@ -92,8 +92,8 @@ def ceilings():
     bq.load()
     dev = torch.device("cuda:0")
     out = torch.empty(256 * 512, device=dev)
-    peaks = {"f32": 157.3, "bf16": 2500.0, "f16": 2500.0, "f64": 78.6}
-    iters = {"f32": 32000, "bf16": 64000, "f16": 64000, "f64": 16000}
+    peaks = {"f32": 157.3, "bf16": 2500.0, "f16": 2500.0, "f64": 78.6, "i8": 5000.0}
+    iters = {"f32": 32000, "bf16": 64000, "f16": 64000, "f64": 16000, "i8": 64000}
     res = {"unit": "TFLOP/s", "mfma": [], "peaks": peaks}
 
     def timed(fn, reps=10):
@@ -106,7 +106,7 @@ def ceilings():
         ms = sorted(a.elapsed_time(b) for a, b in ev[reps // 2:])      # the later half: settled clocks
         return ms[len(ms) // 2]
 
-    for kind in ("f32", "bf16", "f16", "f64"):
+    for kind in ("f32", "bf16", "f16", "f64", "i8"):
         for data in ("zeros", "ones", "normal"):
             for waves in (1, 2):
                 flops = [0.0]
@@ -257,7 +257,7 @@ def main():
         src = X.view(-1)[: (1 << 28)]                 # 2^28 floats = 1 GiB read, 1 GiB written
         dst = torch.empty_like(src)
         for _ in range(3):
-            torch.mul(src, 2.0, out=dst)
+            bq.bpdq_probe_copy(src, dst)              # bpdq::probe_copy_kernel: the scale for the HBM counters
         del dst
     for _ in range(args.warmup):
         step(False)

@@ -249,7 +249,8 @@ int bpdq_gather_symmetric(const float* H, int d_in, const int* perm, float* Hp, 
  * sustains as well as against its published peak.
  * bpdq_probe_mfma: a register-only loop of one matrix-core instruction, no memory traffic:
  *   kind 0 v_mfma_f32_32x32x2_f32, 1 v_mfma_f32_32x32x16_bf16, 2 v_mfma_f32_32x32x16_f16,
- *   3 v_mfma_f64_16x16x4_f64;  data 0 zeros, 1 ones, 2 standard normal operand values (the
+ *   3 v_mfma_f64_16x16x4_f64, 4 v_mfma_i32_32x32x32_i8 (ops instead of flops; normal operands are
+ *   round(32 z) clamped to +-127);  data 0 zeros, 1 ones, 2 standard normal operand values (the
  *   sustained clock depends on the operand bits that toggle);  waves_per_simd 1 or 2;
  *   `groups` work-groups (256 = one per compute unit) of 4 * waves_per_simd wavefronts, each
  *   issuing 8 * iters instructions on a 2 x 4 grid of independent accumulator tiles (fp64: 16 * iters

@@ -410,7 +410,7 @@ def bpdq_gemv(planes, coefs_h, group, x, y=None):
     return y
 
 
-PROBE_KINDS = {"f32": 0, "bf16": 1, "f16": 2, "f64": 3}
+PROBE_KINDS = {"f32": 0, "bf16": 1, "f16": 2, "f64": 3, "i8": 4}
 PROBE_DATA = {"zeros": 0, "ones": 1, "normal": 2}
 
 

@@ -30,7 +30,9 @@ __device__ __forceinline__ float probe_value(int data, unsigned seed) {
   return sqrtf(-2.0f * __logf(u1)) * __cosf(6.2831853f * u2);
 }
 
-enum : int { kProbeF32 = 0, kProbeBF16 = 1, kProbeF16 = 2, kProbeF64 = 3 };
+enum : int { kProbeF32 = 0, kProbeBF16 = 1, kProbeF16 = 2, kProbeF64 = 3, kProbeI8 = 4 };
+typedef int i32x16 __attribute__((ext_vector_type(16)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 
 template <int KIND>
 __global__ __launch_bounds__(512) void probe_mfma_kernel(int iters, int data, float* __restrict__ out) {
@@ -98,6 +100,44 @@ __global__ __launch_bounds__(512) void probe_mfma_kernel(int iters, int data, fl
       for (int j = 0; j < 4; ++j)
 #pragma unroll
         for (int r = 0; r < 16; ++r) sum += c[i][j][r];
+  } else if constexpr (KIND == kProbeI8) {
+    // v_mfma_i32_32x32x32_i8: 16 signed bytes per lane and operand; "normal" = round(32 z) clamped
+    i32x4 a[2], b[4];
+    i32x16 c[2][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        unsigned pa = 0, pb = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float va = probe_value(data, tid * 128 + i * 16 + w * 4 + e) * (data == 2 ? 32.f : 1.f);
+          const float vb = probe_value(data, tid * 128 + 64 + i * 16 + w * 4 + e) * (data == 2 ? 32.f : 1.f);
+          pa |= ((unsigned)(int)fminf(fmaxf(rintf(va), -127.f), 127.f) & 0xffu) << (8 * e);
+          pb |= ((unsigned)(int)fminf(fmaxf(rintf(vb), -127.f), 127.f) & 0xffu) << (8 * e);
+        }
+        if (i < 2) a[i][w] = (int)pa;
+        b[i][w] = (int)pb;
+      }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) c[i][j][r] = 0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          c[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], c[i][j], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum += (float)c[i][j][r];
   } else {
     double a[4], b[4];
     f64x4 c[4][4];
@@ -143,6 +183,7 @@ static double probe_flops_per_mfma(int kind) {
     case kProbeF32: return 2.0 * 32 * 32 * 2;
     case kProbeBF16:
     case kProbeF16: return 2.0 * 32 * 32 * 16;
+    case kProbeI8: return 2.0 * 32 * 32 * 32;
     default: return 2.0 * 16 * 16 * 4;
   }
 }
@@ -150,7 +191,7 @@ static double probe_flops_per_mfma(int kind) {
 extern "C" int bpdq_probe_mfma(int kind, int data, int waves_per_simd, int groups, int iters,
                                float* out, double* flops, void* stream_) {
   hipStream_t stream = static_cast<hipStream_t>(stream_);
-  if (kind < 0 || kind > 3) return -1;
+  if (kind < 0 || kind > 4) return -1;
   if (data < 0 || data > 2) return -2;
   if (waves_per_simd != 1 && waves_per_simd != 2) return -3;
   if (groups < 1 || groups > 65536) return -4;
@@ -166,6 +207,9 @@ extern "C" int bpdq_probe_mfma(int kind, int data, int waves_per_simd, int group
       break;
     case kProbeF16:
       hipLaunchKernelGGL(probe_mfma_kernel<kProbeF16>, dim3(groups), dim3(threads), 0, stream, iters, data, out);
+      break;
+    case kProbeI8:
+      hipLaunchKernelGGL(probe_mfma_kernel<kProbeI8>, dim3(groups), dim3(threads), 0, stream, iters, data, out);
       break;
     default:
       hipLaunchKernelGGL(probe_mfma_kernel<kProbeF64>, dim3(groups), dim3(threads), 0, stream, iters, data, out);
