@@ -421,15 +421,25 @@ __device__ __forceinline__ void level_table(const float (&c)[K + 1], float (&lv)
 //   * the update of block q-1 to the columns beyond block q is a GEMM that extra work-groups of
 //     the first group launch of block q perform (the "tail role"): it only needs E* committed
 //     before the launch and touches no column the launch's sweep reads, so it overlaps the
-//     latency-bound sweep instead of waiting between two of them.
-struct TailArgs {
-  const float* Et;   // Eall + k0 * lde
-  int Kd;            // depth of the update (columns of the finished block)
-  int k0;            // first column of the finished block (row of U)
-  float* Wp;         // working copy W'
+//     latency-bound sweep instead of waiting between two of them;
+//   * two levels: that per-block update (depth B) only reaches to the end of the NEXT super-block
+//     (about 1024 columns per super-block); the columns beyond receive one deep update per finished
+//     super-block (depth ~1024: an eighth of the traffic on W' per flop, and long enough to
+//     amortise a tile's prologue), dealt in column chunks to the group launches of the following
+//     super-block.  The two updates of one launch never touch the same columns (see the host loop).
+//     Only the order of summation differs from one update per block.
+struct TailTask {
+  const float* Et;     // Eall + k0 * lde
+  int Kd;              // depth of the update (finished columns)
+  int k0;              // first finished column (row of U)
   int c_begin, c_end;  // columns [c_begin, c_end) of W' to update
-  int tiles_n;       // column tiles; 0 = no tail work in this launch
-  int first_wg;      // work-groups below this index sweep
+  int tiles_n;         // column tiles; 0 = nothing to do
+};
+struct TailArgs {
+  TailTask far, near;  // deep update of a finished super-block / update of the previous block
+  float* Wp;           // working copy W'
+  int first_wg;        // work-groups below this index sweep
+  int far_wgs;         // tail work-groups [first_wg, first_wg + far_wgs) take `far`, the rest `near`
 };
 
 // Layers that share one input share U and go through the sweep stacked by rows; the best
@@ -443,15 +453,18 @@ struct SegArgs {
 // W'[:, c_begin:c_end] -= Et^T U[k0:k0+Kd, c_begin:c_end], one 128 x 128 tile per work-group
 __device__ __forceinline__ void tail_role(const TailArgs& ta, const float* __restrict__ U, int ldu,
                                           int lde, int ldw, int d_out) {
-  const int t = blockIdx.x - ta.first_wg;
-  const int tm = t / ta.tiles_n, tn = t % ta.tiles_n;
+  int t = blockIdx.x - ta.first_wg;
+  const bool is_far = t < ta.far_wgs;          // uniform over the work-group
+  if (!is_far) t -= ta.far_wgs;
+  const TailTask& task = is_far ? ta.far : ta.near;
+  const int tm = t / task.tiles_n, tn = t % task.tiles_n;
   TailGemm::Acc acc;
   TailGemm::zero(acc);
-  TailGemm::run<0>(ta.Et, lde, tm * TailGemm::kTileM, lde, U + (long)ta.k0 * ldu, ldu,
-                   ta.c_begin + tn * TailGemm::kTileN, ta.c_end, 0, ta.Kd, acc);
-  const int r0 = tm * TailGemm::kTileM, c0 = ta.c_begin + tn * TailGemm::kTileN;
+  TailGemm::run<0>(task.Et, lde, tm * TailGemm::kTileM, lde, U + (long)task.k0 * ldu, ldu,
+                   task.c_begin + tn * TailGemm::kTileN, task.c_end, 0, task.Kd, acc);
+  const int r0 = tm * TailGemm::kTileM, c0 = task.c_begin + tn * TailGemm::kTileN;
   float* Wp = ta.Wp;
-  const int c_end = ta.c_end;
+  const int c_end = task.c_end;
   // in-place read-modify-write of this lane's 64 results: all loads first (masked elements read
   // a valid address and are not stored), then the stores
   float old[TailGemm::kAccPerLane];
@@ -909,7 +922,9 @@ static inline int launch_group(hipStream_t stream, const float* Wp, int d_out, i
   const bool uniform = (p.grid == BPDQ_GRID_UNIFORM);
   const int T = uniform ? 0 : p.refine_iters;
   ta.first_wg = L.n_wg;
-  int n_tail = ta.tiles_n > 0 ? bpdq_ceil_div(L.lde, TailGemm::kTileM) * ta.tiles_n : 0;
+  const int row_tiles = bpdq_ceil_div(L.lde, TailGemm::kTileM);
+  ta.far_wgs = row_tiles * ta.far.tiles_n;
+  int n_tail = row_tiles * (ta.far.tiles_n + ta.near.tiles_n);
   if (!kTailInSweep<G> && n_tail > 0) {
     const int rc = launch_tail_update(stream, ta, U, d_in, L.lde, d_in, d_out, n_tail);
     if (rc) return rc;

@@ -16,6 +16,7 @@ int launch_tail_update(hipStream_t stream, TailArgs ta, const float* U, int ldu,
                        int d_out, int n_tiles) {
   BPDQ_HIP_TRY(bpdq_lds_limit<&tail_update_kernel>(TailGemm::kLdsBytes));
   ta.first_wg = 0;
+  ta.far_wgs = bpdq_ceil_div(lde, TailGemm::kTileM) * ta.far.tiles_n;
   hipLaunchKernelGGL(tail_update_kernel, dim3(n_tiles), dim3(TailGemm::kThreads), TailGemm::kLdsBytes,
                      stream, ta, U, ldu, lde, ldw, d_out);
   BPDQ_LAUNCH_CHECK();
@@ -153,20 +154,49 @@ static int quantize_rows(const float* W, int d_out, int d_in, const float* U,
   // block late: the first group launch of block q carries the update of block q-1 to the columns
   // beyond block q (tail role), and every group of block q reads the updates of block q-1 and of
   // the earlier groups of its own block left-looking from the committed E*.
+  // Two levels (see TailArgs): with super-blocks of SBc columns, the update of a block of
+  // super-block S reaches only to the end of super-block S + 1; the columns from super-block S + 2
+  // on receive ONE update of depth SBc for all of super-block S, applied during the launches of
+  // super-block S + 1: its first launch takes the columns of super-block S + 2 (the per-block
+  // update of that launch, from the last block of S, ends where they begin), the other launches
+  // share the columns beyond (which no per-block update of super-block S + 1 reaches).  Two
+  // updates of one launch thus never meet, and a column has received every earlier block's term
+  // before its own block starts.
   const int g = p->group, B = L.B;
+  const int SBc = B >= 1024 ? B : B * (1024 / B);
+  auto make_task = [&](int k0, int Kd, long c0, long c1) {
+    TailTask t{};
+    c0 = c0 < d_in ? c0 : d_in;
+    c1 = c1 < d_in ? c1 : d_in;
+    if (c1 > c0) {
+      t.Et = Eall + (long)k0 * L.lde;
+      t.Kd = Kd;
+      t.k0 = k0;
+      t.c_begin = (int)c0;
+      t.c_end = (int)c1;
+      t.tiles_n = bpdq_ceil_div((int)(c1 - c0), TailGemm::kTileN);
+    }
+    return t;
+  };
   for (int b0 = 0; b0 < d_in; b0 += B) {
     const int b1 = b0 + B < d_in ? b0 + B : d_in;
     const int kp0 = b0 > 0 ? b0 - B : 0;
+    const int sb0 = b0 / SBc * SBc;                         // start of this block's super-block
     for (int s0 = b0; s0 < b1; s0 += g) {
       TailArgs ta{};
-      if (s0 == b0 && b0 > 0 && b1 < d_in) {
-        ta.Et = Eall + (long)kp0 * L.lde;
-        ta.Kd = B;
-        ta.k0 = kp0;
-        ta.Wp = Wp;
-        ta.c_begin = b1;
-        ta.c_end = d_in;
-        ta.tiles_n = bpdq_ceil_div(d_in - b1, TailGemm::kTileN);
+      ta.Wp = Wp;
+      if (s0 == b0 && b0 > 0)     // per-block update of block q-1: to the end of the super-block after its own
+        ta.near = make_task(kp0, B, b1, ((long)(kp0 / SBc) + 2) * SBc);
+      if (sb0 > 0) {
+        // deep update of the previous super-block [sb0 - SBc, sb0), columns from sb0 + SBc on
+        const int li = (s0 - sb0) / g, n_l = SBc / g;
+        const long f0 = (long)sb0 + SBc, f1 = f0 + SBc;      // the next super-block's columns
+        if (li == 0) {
+          ta.far = make_task(sb0 - SBc, SBc, f0, f1);
+        } else if (f1 < d_in) {
+          const int cols = bpdq_ceil_div(bpdq_ceil_div(d_in - (int)f1, TailGemm::kTileN), n_l - 1) * TailGemm::kTileN;
+          ta.far = make_task(sb0 - SBc, SBc, f1 + (long)(li - 1) * cols, f1 + (long)li * cols);
+        }
       }
       const int rc = group(stream, Wp, d_out, d_in, U, s0, kp0, ta, seg, *p, L, base, planes, coefs,
                            W_hat, grp_err, grp_iter);
@@ -245,14 +275,14 @@ extern "C" int bpdq_block_update(const float* Et, int lde, int Kd, const float* 
   if (c_end < c_begin || c_end % 4) return -11;
   if (c_end == c_begin) return 0;
   TailArgs ta{};
-  ta.Et = Et;
-  ta.Kd = Kd;
-  ta.k0 = k0;
   ta.Wp = Wp;
-  ta.c_begin = c_begin;
-  ta.c_end = c_end;
-  ta.tiles_n = bpdq_ceil_div(c_end - c_begin, TailGemm::kTileN);
-  const int n_tiles = bpdq_ceil_div(d_out, TailGemm::kTileM) * ta.tiles_n;
+  ta.near.Et = Et;
+  ta.near.Kd = Kd;
+  ta.near.k0 = k0;
+  ta.near.c_begin = c_begin;
+  ta.near.c_end = c_end;
+  ta.near.tiles_n = bpdq_ceil_div(c_end - c_begin, TailGemm::kTileN);
+  const int n_tiles = bpdq_ceil_div(lde, TailGemm::kTileM) * ta.near.tiles_n;
   return launch_tail_update(static_cast<hipStream_t>(stream_), ta, U, ldu, lde, ldw, d_out, n_tiles);
 }
 
