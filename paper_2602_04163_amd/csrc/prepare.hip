@@ -101,64 +101,85 @@ __device__ __forceinline__ void put_tile64(ROW* s, const double (&v)[16]) {
   }
 }
 
-// Reversed Cholesky of one 64 x 64 block held in registers: D = R R^T, R upper, columns taken
-// from the last to the first.  Thread (ty, tx) of 256 keeps the 4 x 4 sub-block rows 4ty..,
-// cols 4tx.. in `a` (the full symmetric block).  Per column: one LDS broadcast of the current
-// column, one barrier, one reciprocal and a rank-1 update  a -= col col^T / pivot.  On return
-// (after a barrier) sR holds R (zero below the diagonal) and sInvD[j] = 1 / R_jj; the square
-// roots are taken once, off the critical path.  A non-positive pivot is reported as column
-// p0 + j + 1 (by the work-group with `report`) and replaced by 1.
-__device__ __forceinline__ void factor64(double (&a)[4][4], double (*sR)[NB + 1],
-                                         double (*col)[NB], double* sInvD, int* info, int p0,
-                                         bool report) {
-  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+
+// Reversed Cholesky of one 64 x 64 block held in LDS: D = R R^T, R upper, columns taken from the
+// last to the first, in panels of 16 columns.
+//   in : sD, the full symmetric block (both triangles; identity padding where the block is ragged)
+//   out: sD = R (zero below the diagonal), sInvD[j] = 1 / R_jj
+// A panel is factored by ONE wavefront, lane r holding row r of its 16 columns in registers: a
+// column step writes the pivot column to LDS and reads the pivot and the (at most 15) entries it
+// needs back as broadcasts -- LDS serves one wavefront in order, so no barrier is involved -- then
+// updates only the panel's columns left of the pivot.  The other columns of the block receive the
+// panel's rank-16 update afterwards on the fp64 matrix cores (all four wavefronts).  Against a
+// column step that updates the whole block (16 multiply-adds per thread of 256 behind a barrier)
+// the dependent chain per column is a third as long.  Square roots are taken once, at the end.
+// A non-positive pivot is reported as column p0 + j + 1 (by the work-group with `report`) and
+// replaced by 1.  All 256 threads call this; sCol and sPiv are 64 doubles each.
+template <int JL>
+__device__ __forceinline__ void factor_panel_step(double (&pa)[16], double* sCol, double* sPiv, int c0,
+                                                  int lane, int* info, int p0, bool report) {
+  sCol[lane] = pa[JL];
+  const double piv_raw = sCol[c0 + JL];
+  double cc[JL > 0 ? JL : 1];
+#pragma unroll
+  for (int e = 0; e < JL; ++e) cc[e] = sCol[c0 + e];
+  const bool bad = !(piv_raw > 0.0);
+  const double piv = bad ? 1.0 : piv_raw;
+  const double t = pa[JL] * fast_rcp(piv);
+#pragma unroll
+  for (int e = 0; e < JL; ++e) pa[e] = fma(-t, cc[e], pa[e]);
+  if (lane == 0) {
+    sPiv[c0 + JL] = piv;
+    if (bad && report) atomicCAS(info, 0, p0 + c0 + JL + 1);
+  }
+  if constexpr (JL > 0) factor_panel_step<JL - 1>(pa, sCol, sPiv, c0, lane, info, p0, report);
+}
+
+__device__ __forceinline__ void factor64_blocked(double (*sD)[NB + 1], double* sCol, double* sPiv,
+                                                 double* sInvD, int* info, int p0, bool report) {
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
 #pragma unroll 1
-  for (int jb = NB / 4 - 1; jb >= 0; --jb) {
+  for (int J = NB / 16 - 1; J >= 0; --J) {
+    const int c0 = 16 * J;
+    __syncthreads();                        // the block, with every earlier panel's update, is in LDS
+    if (w == 0) {
+      double pa[16];
 #pragma unroll
-    for (int jj = 3; jj >= 0; --jj) {
-      const int j = 4 * jb + jj;
-      double* cbuf = col[j & 1];
-      if (tx == jb) {
+      for (int e = 0; e < 16; ++e) pa[e] = sD[lane][c0 + e];
+      factor_panel_step<15>(pa, sCol, sPiv, c0, lane, info, p0, report);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) cbuf[4 * ty + r] = a[r][jj];
-      }
-      __syncthreads();
-      // every LDS read of the step is issued before the first is used: one round trip, not three
-      const double piv_raw = cbuf[j];
-      double ci[4], cj[4];
-#pragma unroll
-      for (int r = 0; r < 4; ++r) ci[r] = cbuf[4 * ty + r];
-#pragma unroll
-      for (int c = 0; c < 4; ++c) cj[c] = cbuf[4 * tx + c];
-      const double mine = cbuf[tid & (NB - 1)];
-      const bool bad = !(piv_raw > 0.0);
-      const double piv = bad ? 1.0 : piv_raw;
-      const double ip = fast_rcp(piv);
-#pragma unroll
-      for (int r = 0; r < 4; ++r) ci[r] *= ip;
-#pragma unroll
-      for (int r = 0; r < 4; ++r)
-#pragma unroll
-        for (int c = 0; c < 4; ++c) a[r][c] = fma(-ci[r], cj[c], a[r][c]);
-      // off the critical chain: the finished column (unscaled; scaled after the loop), the pivot
-      if (tid < NB) {
-        sR[tid][j] = (tid <= j) ? mine : 0.0;
-        if (tid == j) sInvD[j] = piv;
-      }
-      if (bad && tid == 0 && report) atomicCAS(info, 0, p0 + j + 1);
+      for (int e = 0; e < 16; ++e) sD[lane][c0 + e] = (lane <= c0 + e) ? pa[e] : 0.0;   // unscaled columns of R
     }
+    __syncthreads();
+    // leading block [0, c0) x [0, c0), upper 16 x 16 tiles:  -= Rp diag(1 / pivot) Rp^T
+    const int m = lane & 15, kq = lane >> 4;
+    int t = 0;
+    for (int tk = 0; tk < J; ++tk)
+      for (int ti = 0; ti <= tk; ++ti, ++t) {
+        if ((t & 3) != w) continue;
+        f64x4 acc = (f64x4){0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+          const int kk = c0 + 4 * ks + kq;
+          const double a = sD[16 * ti + m][kk] * fast_rcp(sPiv[kk]);
+          const double b = sD[16 * tk + m][kk];
+          acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) sD[16 * ti + 4 * r + kq][16 * tk + m] -= acc[r];
+      }
   }
   __syncthreads();
-  if (tid < NB) sInvD[tid] = 1.0 / sqrt(sInvD[tid]);
+  if (tid < NB) sInvD[tid] = 1.0 / sqrt(sPiv[tid]);
   __syncthreads();
   for (int e = tid; e < NB * NB; e += 256) {
     const int i = e / NB, j = e % NB;
-    sR[i][j] *= sInvD[j];                              // R[:, j] = column_j / sqrt(pivot_j)
+    sD[i][j] = (i <= j) ? sD[i][j] * sInvD[j] : 0.0;          // R[:, j] = column_j / sqrt(pivot_j)
   }
   __syncthreads();
 }
 
-typedef double f64x4 __attribute__((ext_vector_type(4)));
 
 // X R^T = A for one or two 64 x 64 tiles at once, in place, by blocks of 16 columns from the
 // right (R upper, sInvD[j] = 1 / R_jj):
@@ -217,21 +238,19 @@ __device__ __forceinline__ void trsm64_blocked(double (*sXa)[NB + 1], double (*s
   }
 }
 
-// The symmetric 64 x 64 block at (p0, p0) into the register tiling of factor64 (only the upper
-// triangle of A is valid); identity padding beyond nb.
-__device__ __forceinline__ void load_diag_block(const double* __restrict__ A, int d, int p0, int nb,
-                                                double (&a)[4][4]) {
-  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+// The symmetric 64 x 64 block at (p0, p0), both triangles (only the upper triangle of A is valid),
+// identity padding beyond nb: 16 elements per thread in the order of fetch_tile64 / put_tile64.
+__device__ __forceinline__ void fetch_diag_block(const double* __restrict__ A, int d, int p0, int nb,
+                                                 double (&v)[16]) {
 #pragma unroll
-  for (int r = 0; r < 4; ++r)
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const int i = 4 * ty + r, j = 4 * tx + c;
-      const bool in = i < nb && j < nb;
-      const int lo = i < j ? i : j, hi = i < j ? j : i;
-      const double x = A[in ? (long)(p0 + lo) * d + p0 + hi : 0L];
-      a[r][c] = in ? x : ((i == j) ? 1.0 : 0.0);
-    }
+  for (int t = 0; t < 16; ++t) {
+    const int e = threadIdx.x + 256 * t;
+    const int i = e >> 6, j = e & 63;
+    const bool in = i < nb && j < nb;
+    const int lo = i < j ? i : j, hi = i < j ? j : i;
+    const double x = A[in ? (long)(p0 + lo) * d + p0 + hi : 0L];
+    v[t] = in ? x : ((i == j) ? 1.0 : 0.0);
+  }
 }
 
 // Panel step of the reversed Cholesky for ONE 64-column panel, one work-group (256 threads) per
@@ -251,8 +270,11 @@ __global__ __launch_bounds__(256) void panel_factor_kernel(double* __restrict__ 
   __shared__ double sInvD[NB];
   const int tid = threadIdx.x;
 
-  double a[4][4];
-  load_diag_block(A, d, p0, nb, a);
+  {
+    double v[16];
+    fetch_diag_block(A, d, p0, nb, v);
+    put_tile64(sR, v);
+  }
   // panel tile (coalesced), used after the factorisation
   const int r0 = blockIdx.x * NB;
   if (n_above > 0) {
@@ -261,7 +283,7 @@ __global__ __launch_bounds__(256) void panel_factor_kernel(double* __restrict__ 
                  [&](int i, int j) { return (long)(r0 + i) * d + p0 + j; }, v);
     put_tile64(sA, v);
   }
-  factor64(a, sR, col, sInvD, info, p0, blockIdx.x == 0);
+  factor64_blocked(sR, col[0], col[1], sInvD, info, p0, blockIdx.x == 0);
   // R of the diagonal block goes to its own buffer: the block itself must stay untouched, because
   // work-groups of this launch that start later still have to read it
   if (blockIdx.x == 0) {
@@ -408,11 +430,12 @@ __global__ __launch_bounds__(256) void panel_pair_kernel(double* __restrict__ A,
   const int r0 = blockIdx.x * NB;
   const bool first = blockIdx.x == 0;
 
-  double a[4][4], a1[4][4];
-  load_diag_block(A, d, p2, nb2, a);                // D22
-  load_diag_block(A, d, p1, NB, a1);                // D11, needed after the first factorisation
+  double d11[16];                                   // D11, needed after the first factorisation
+  fetch_diag_block(A, d, p1, NB, d11);
   {
-    double v12[16], v1[16], v2[16];
+    double v22[16], v12[16], v1[16], v2[16];
+    fetch_diag_block(A, d, p2, nb2, v22);           // D22
+    put_tile64(sR, v22);
     fetch_tile64(A, [&](int, int j) { return j < nb2; },
                  [&](int i, int j) { return (long)(p1 + i) * d + p2 + j; }, v12);
     if (n_above > 0) {
@@ -425,7 +448,7 @@ __global__ __launch_bounds__(256) void panel_pair_kernel(double* __restrict__ A,
     }
     put_tile64(sR12, v12);
   }
-  factor64(a, sR, col, sInvD, info, p2, first);
+  factor64_blocked(sR, col[0], col[1], sInvD, info, p2, first);
   if (first)
     for (int e = tid; e < NB * NB; e += 256) Rdiag2[e] = sR[e / NB][e % NB];
   // R12 = D12 R22^-T and X2 = A2 R22^-T
@@ -435,7 +458,7 @@ __global__ __launch_bounds__(256) void panel_pair_kernel(double* __restrict__ A,
     Quad64 q;
     quad_zero(q);
     quad_mfma_64<true>(sR12, sR12, q);              // R12 R12^T
-    quad_for_each(q, [&](int r, int c, double v) { sR[r][c] = v; });
+    quad_for_each(q, [&](int r, int c, double v) { sR[r][c] = -v; });     // (R22 is no longer needed)
     if (n_above > 0) {
       quad_zero(q);
       quad_mfma_64<true>(sA2, sR12, q);             // X2 R12^T
@@ -444,10 +467,11 @@ __global__ __launch_bounds__(256) void panel_pair_kernel(double* __restrict__ A,
   }
   __syncthreads();
 #pragma unroll
-  for (int r = 0; r < 4; ++r)
-#pragma unroll
-    for (int c = 0; c < 4; ++c) a1[r][c] -= sR[4 * ty + r][4 * tx + c];
-  factor64(a1, sR, col, sInvD, info, p1, first);    // its first barrier precedes any write to sR
+  for (int t = 0; t < 16; ++t) {                    // sR = D11 - R12 R12^T
+    const int e = tid + 256 * t;
+    sR[e >> 6][e & 63] += d11[t];
+  }
+  factor64_blocked(sR, col[0], col[1], sInvD, info, p1, first);
   if (first) {
     for (int e = tid; e < NB * NB; e += 256) {
       Rdiag1[e] = sR[e / NB][e % NB];
