@@ -342,6 +342,9 @@ __global__ __launch_bounds__(256) void diag_inverse_kernel(const double* __restr
   for (int e = tid; e < NB * NB; e += 256) {
     const int i = e / NB, j = e % NB;
     if (i < nb && j < nb) A[(long)(p0 + i) * d + p0 + j] = (j >= i) ? x[i][j] : 0.0;
+    // the block to the left of the diagonal one: the 128-tile products of the inversion read it as
+    // part of a triangular operand, where it stands for zeros
+    if (p0 > 0 && i < nb) A[(long)(p0 + i) * d + p0 - NB + j] = 0.0;
   }
 }
 
@@ -544,6 +547,224 @@ __global__ __launch_bounds__(256) void syrk_trailing_kernel(double* __restrict__
   });
 }
 
+// ---- fp64 products on 128 x 128 tiles, operands streamed to LDS by the DMA path -------------
+// For the wide layers.  A 64 x 64 tile moves 2 x 64 operand rows per 64 x 64 results, which at
+// the fp64 matrix rate is more than the caches deliver, and its loads pass through registers,
+// whose address arithmetic and LDS writes sit between the matrix instructions.  Here 256 threads
+// own 128 x 128 results, wavefront w the 64 x 64 quadrant (w / 2, w % 2) as 4 x 4 tiles of
+// v_mfma_f64_16x16x4_f64, and both operands reach LDS in slices of 16 along K through the LDS-DMA
+// path (global_load_lds_dwordx4: 64 lanes x 16 bytes land in 1 KB of LDS, no registers involved),
+// double-buffered: the requests for slice s + 1 go out right behind the first operand reads of
+// slice s.  64 KB of LDS and fewer than 256 registers: two work-groups per compute unit.
+//
+// LDS image of a slice of an operand given by rows ([row][k], k contiguous in memory): row r
+// (128 bytes = 8 pairs of doubles) keeps pair p at position p ^ ((r / 2) % 8).  The DMA writes
+// lane-linear, so the lane that fills position q of row r fetches pair q ^ ((r / 2) % 8).  An
+// operand read (16 rows x one column per quarter wave) then touches 16 distinct bank pairs;
+// unswizzled, rows 128 bytes apart would share two.
+// LDS image of a slice of an operand given as [k][n] (n contiguous): k-row k (1 KB = 64 pairs)
+// keeps pair c at position c ^ (8 (k % 2)), so that the two k-rows a half wave reads lie in
+// different halves of the banks.
+//
+// Requirements (the launchers fall back to the 64-tile kernels otherwise): even leading
+// dimensions and 16-byte aligned slices; K ranges that are multiples of 32.  Rows (columns) past
+// an operand's limit are clamped to a valid one: their products land in results never stored.
+constexpr int kGemmTile = 128;
+constexpr int kGemmK = 16;
+constexpr unsigned kGemmOpBytes = kGemmTile * kGemmK * sizeof(double);       // one operand slice
+constexpr unsigned kGemmStageBytes = 2 * kGemmOpBytes;
+constexpr size_t kGemmLdsBytes = 2 * kGemmStageBytes;
+
+struct Acc128 {
+  f64x4 c[4][4];
+};
+
+// 64 lanes x 16 bytes from gptr (per lane) to the 1 KB of LDS at byte address lds_addr (uniform,
+// passed in M0, which these kernels use for nothing else).  One outstanding vector-memory operation.
+__device__ __forceinline__ void dma_1k_f64(const double* gptr, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(gptr) : "memory");
+}
+__device__ __forceinline__ void wait_all_vm() {
+  __builtin_amdgcn_s_waitcnt(0x0070 | 0x0f00);      // vmcnt 0; expcnt / lgkmcnt at their maxima
+}
+
+// DMA sources of wavefront w for slice 0 of an operand given by rows: rows [32 w, 32 w + 32) of the
+// tile that starts at row0, 8 rows per request.
+__device__ __forceinline__ void gemm128_row_sources(const double* base, long ld, int row0, int row_limit,
+                                                    int k_begin, int w, int lane, const double* (&src)[4]) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int r = 32 * w + 8 * j + (lane >> 3);
+    const int pair = (lane & 7) ^ ((r >> 1) & 7);
+    const int g = (row0 + r < row_limit) ? row0 + r : row_limit - 1;
+    src[j] = base + (long)g * ld + k_begin + 2 * pair;
+  }
+}
+// ... of an operand given as [k][n]: k-rows [4 w, 4 w + 4) of the slice, columns [col0, col0 + 128)
+__device__ __forceinline__ void gemm128_col_sources(const double* base, long ld, int k_begin, int col0,
+                                                    int col_limit, int w, int lane, const double* (&src)[4]) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int pair = lane ^ ((j & 1) << 3);                    // (4 w + j) % 2 == j % 2
+    const int col = (col0 + 2 * pair < col_limit) ? col0 + 2 * pair : col0;
+    src[j] = base + (long)(k_begin + 4 * w + j) * ld + col;
+  }
+}
+
+// q += A B over n_stage (even) slices.  B_ROWS: B is given by rows like A (C = A B^T, the SYRK
+// form), else as [k][n].  step_a / step_b: elements between consecutive slices of a source.
+template <bool B_ROWS>
+__device__ __forceinline__ void gemm128_accumulate(const double* const (&src_a)[4], const double* const (&src_b)[4],
+                                                   long step_a, long step_b, int n_stage, Acc128& q) {
+  extern __shared__ __align__(16) double gemm128_lds[];
+  typedef __attribute__((address_space(3))) double lds_f64;
+  const int lane = threadIdx.x & 63;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const unsigned lds0 = (unsigned)(size_t)(lds_f64*)gemm128_lds;
+  auto request = [&](int s) {
+    const unsigned slot = lds0 + (unsigned)(s & 1) * kGemmStageBytes + (unsigned)w * 4096u;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) dma_1k_f64(src_a[j] + s * step_a, slot + j * 1024u);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) dma_1k_f64(src_b[j] + s * step_b, slot + kGemmOpBytes + j * 1024u);
+  };
+  // operand reads: lane (m = lane % 16, kq = lane / 16) takes column 4 t + kq of rows m + 16 i
+  const int l15 = lane & 15, kq = lane >> 4;
+  const unsigned sw = (unsigned)((((kq >> 1) ^ (l15 >> 1)) << 4) | ((kq & 1) << 3));
+  unsigned a_off[4], b_off[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    a_off[t] = ((unsigned)(((w >> 1) * 64 + l15) * 128) + sw) ^ (unsigned)(32 * t);
+    b_off[t] = kGemmOpBytes + (((unsigned)(((w & 1) * 64 + l15) * 128) + sw) ^ (unsigned)(32 * t));
+  }
+  // [k][n] form: byte = 1024 k + 16 (pair ^ 8 (k % 2)) + 8 (n % 2) with k = 4 t + kq, n = 64 (w % 2) + 16 j + m
+  const unsigned b_base = kGemmOpBytes + (unsigned)(kq * 1024 + (w & 1) * 512 + l15 * 8);
+  const unsigned b_even = b_base + (unsigned)((kq & 1) * 128), b_odd = b_base + (unsigned)(((kq & 1) ^ 1) * 128);
+  const char* const lds_bytes = reinterpret_cast<const char*>(gemm128_lds);
+  auto compute = [&](unsigned stage_off, int next) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      double a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        a[i] = *reinterpret_cast<const double*>(lds_bytes + stage_off + a_off[t] + i * 2048);
+        if constexpr (B_ROWS)
+          b[i] = *reinterpret_cast<const double*>(lds_bytes + stage_off + b_off[t] + i * 2048);
+        else
+          b[i] = *reinterpret_cast<const double*>(lds_bytes + stage_off + ((i & 1) ? b_odd : b_even) + t * 4096 +
+                                                  (i >> 1) * 256);
+      }
+      if (t == 0 && next >= 0) request(next);      // behind the first reads, ahead of the products
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          q.c[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], q.c[i][j], 0, 0, 0);
+    }
+  };
+  if (n_stage <= 0) return;
+  request(0);
+  for (int s = 0; s < n_stage; s += 2) {
+    wait_all_vm();                                 // this wavefront's part of slice s has landed
+    __builtin_amdgcn_s_barrier();                  // ... everyone's has, and slice s - 1 is read out
+    asm volatile("" ::: "memory");
+    compute(0u, s + 1);
+    wait_all_vm();
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    compute(kGemmStageBytes, (s + 2 < n_stage) ? s + 2 : -1);
+  }
+}
+
+// f(i, j, r, row, col): result register r of tile (i, j) of this lane and where it sits in the 128 x 128 tile
+template <typename F>
+__device__ __forceinline__ void acc128_for_each_in_row(int i, F f) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      f(j, r, (w >> 1) * 64 + 16 * i + 4 * r + (lane >> 4), (w & 1) * 64 + 16 * j + (lane & 15));
+}
+
+// The trailing update on this engine.  Tile order: the hardware deals work-groups to the 8 dies in
+// turn (work-group b runs on die b % 8, each die with an L2 of its own).  Die x takes the row tiles
+// I = x, x + 8, ... of every band of 4 column tiles, four consecutive work-groups sharing one row
+// strip; a band's four column strips (2 MB at depth 512) stay in that die's L2 while its row tiles
+// stream past.  Needs d even, Kd a multiple of 32, k0 + Kd <= d.
+constexpr int kTrailBand = 4;
+
+// Row tiles of band `band` that die x works on: I = x + 8 n, n < the value returned.  The band's
+// last column is min(cbeg + 128 (4 band + 4), cend) - 1; row tiles beyond it lie below the diagonal.
+__host__ __device__ inline int trail_band_rows(int band, int x, int cbeg, int cend) {
+  long last = (long)cbeg + (long)kGemmTile * kTrailBand * (band + 1);
+  if (last > cend) last = cend;
+  const int i_last = (int)((last - 1) / kGemmTile);
+  return (i_last >= x) ? (i_last - x) / 8 + 1 : 0;
+}
+
+__global__ __launch_bounds__(256, 2) void syrk_trailing128_kernel(double* __restrict__ A, int d, int k0,
+                                                                  int Kd, int cb0, int cb1) {
+  const int cbeg = cb0 * NB, cend = cb1 * NB;
+  const int n_col_tiles = (cend - cbeg + kGemmTile - 1) / kGemmTile;
+  const int n_band = (n_col_tiles + kTrailBand - 1) / kTrailBand;
+  const int x = blockIdx.x & 7;
+  int rem = blockIdx.x >> 3, band = 0;
+  for (; band < n_band; ++band) {
+    const int cnt = trail_band_rows(band, x, cbeg, cend) * kTrailBand;
+    if (rem < cnt) break;
+    rem -= cnt;
+  }
+  if (band == n_band) return;
+  const int tj = band * kTrailBand + (rem & (kTrailBand - 1));
+  if (tj >= n_col_tiles) return;
+  const int row0 = (x + 8 * (rem / kTrailBand)) * kGemmTile;
+  const int col0 = cbeg + tj * kGemmTile;
+  if (row0 > col0 + kGemmTile - 1) return;      // wholly below the diagonal
+
+  const int lane = threadIdx.x & 63;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  Acc128 q;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) q.c[i][j] = (f64x4){0.0, 0.0, 0.0, 0.0};
+  const double* src_i[4];
+  const double* src_j[4];
+  gemm128_row_sources(A, d, row0, cend, k0, w, lane, src_i);
+  gemm128_row_sources(A, d, col0, cend, k0, w, lane, src_j);
+  gemm128_accumulate<true>(src_i, src_j, kGemmK, kGemmK, Kd / kGemmK, q);
+  // read-modify-write, one row of tiles (16 values per lane) at a time, loads first
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    double old[16];
+    acc128_for_each_in_row(i, [&](int j, int r, int row, int col) {
+      const int gi = row0 + row, gj = col0 + col;
+      const bool in = gi < cend && gj < cend && gj >= gi;
+      old[4 * j + r] = A[in ? (long)gi * d + gj : 0L];
+    });
+    acc128_for_each_in_row(i, [&](int j, int r, int row, int col) {
+      const int gi = row0 + row, gj = col0 + col;
+      if (gi < cend && gj < cend && gj >= gi) A[(long)gi * d + gj] = old[4 * j + r] - q.c[i][j][r];
+    });
+  }
+}
+
+// Work-groups of a launch of the 128-tile update over column blocks [cb0, cb1): 8 dies times the
+// longest list, which is die 0's.
+static int trail128_grid(int cb0, int cb1) {
+  const int cbeg = cb0 * NB, cend = cb1 * NB;
+  const int n_col_tiles = (cend - cbeg + kGemmTile - 1) / kGemmTile;
+  const int n_band = (n_col_tiles + kTrailBand - 1) / kTrailBand;
+  int slots = 0;
+  for (int band = 0; band < n_band; ++band) slots += trail_band_rows(band, 0, cbeg, cend) * kTrailBand;
+  return 8 * slots;
+}
+// Below this many column blocks the 64-tile kernel has more work-groups to spread over the chip.
+constexpr int kTrail128MinBlocks = 32;
+// ... and below this many blocks per half of a node, for the products of the inversion
+constexpr int kInverse128MinBlocks = 8;
+
 // ---------------------------------------------------------------- invert -------------------
 // Node `node` of tree depth `depth` over the block range [0, P): ranges are halved
 // (left half gets the extra block).  Returns false if the path ends in a leaf earlier.
@@ -625,6 +846,54 @@ __global__ __launch_bounds__(256) void tri_inverse_level_kernel(double* __restri
   });
 }
 
+// The same two products on the 128-tile engine (d a multiple of 64).  Tile (ti, tj) of 128 x 128:
+//   MODE 1: tmp[rows][tj] = R12[rows][k] U22[k][tj], k over the columns of U22 up to the tile's last
+//           (U22 is upper triangular; the block left of a diagonal block holds zeros);
+//   MODE 2: U12[rows][tj] = -U11[rows][k] tmp[k][tj], k from the tile's first row on.
+// A node with an odd number of blocks leaves half a tile hanging over: its rows / columns are
+// clamped on the way in and skipped on the way out.
+template <int MODE>
+__global__ __launch_bounds__(256, 2) void tri_inverse_level128_kernel(double* __restrict__ A, int d,
+                                                                      double* __restrict__ tmp, int ldt,
+                                                                      int P, int depth) {
+  int lo, mid, hi;
+  if (!tree_node(P, depth, blockIdx.z, lo, mid, hi)) return;
+  const int n_rows = (mid - lo) * NB, n_cols = (hi - mid) * NB;
+  const int r_loc = blockIdx.y * kGemmTile, c_loc = blockIdx.x * kGemmTile;   // inside the node
+  if (r_loc >= n_rows || c_loc >= n_cols) return;
+  const int row0 = lo * NB + r_loc, row_limit = mid * NB;     // global rows of the tile
+  const int col0 = mid * NB + c_loc, col_limit = hi * NB;     // global columns of the tile (in A)
+  const int lane = threadIdx.x & 63;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  Acc128 q;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) q.c[i][j] = (f64x4){0.0, 0.0, 0.0, 0.0};
+  const double* src_a[4];
+  const double* src_b[4];
+  if (MODE == 1) {
+    const int k_begin = mid * NB;
+    const int k_end = (col0 + kGemmTile < col_limit) ? col0 + kGemmTile : col_limit;
+    gemm128_row_sources(A, d, row0, row_limit, k_begin, w, lane, src_a);
+    gemm128_col_sources(A, d, k_begin, col0, col_limit, w, lane, src_b);
+    gemm128_accumulate<false>(src_a, src_b, kGemmK, (long)kGemmK * d, (k_end - k_begin) / kGemmK, q);
+  } else {
+    const int k_begin = row0, k_end = row_limit;
+    gemm128_row_sources(A, d, row0, row_limit, k_begin, w, lane, src_a);
+    gemm128_col_sources(tmp, ldt, k_begin, c_loc, n_cols, w, lane, src_b);
+    gemm128_accumulate<false>(src_a, src_b, kGemmK, (long)kGemmK * ldt, (k_end - k_begin) / kGemmK, q);
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    acc128_for_each_in_row(i, [&](int j, int r, int row, int col) {
+      const int gi = row0 + row;
+      if (gi >= row_limit || c_loc + col >= n_cols) return;
+      if (MODE == 1) tmp[(long)gi * ldt + c_loc + col] = q.c[i][j][r];
+      else A[(long)gi * d + col0 + col] = -q.c[i][j][r];
+    });
+}
+
 // U (fp32) <- upper triangle of A, zeros below.
 __global__ __launch_bounds__(256) void prep_store_kernel(const double* __restrict__ A, int d,
                                                          float* __restrict__ U) {
@@ -693,6 +962,9 @@ extern "C" int bpdq_prepare(const float* H, int d_in, float damp, float* U, unsi
   int* pair_flag = reinterpret_cast<int*>(base + L.flag_off);
   const int d = d_in, P = L.P;
   BPDQ_HIP_TRY(bpdq_lds_limit<&panel_pair_kernel>(kPairLdsBytes));
+  BPDQ_HIP_TRY(bpdq_lds_limit<&syrk_trailing128_kernel>(kGemmLdsBytes));
+  BPDQ_HIP_TRY(bpdq_lds_limit<&tri_inverse_level128_kernel<1>>(kGemmLdsBytes));
+  BPDQ_HIP_TRY(bpdq_lds_limit<&tri_inverse_level128_kernel<2>>(kGemmLdsBytes));
 
   hipLaunchKernelGGL(prep_diag_kernel, dim3(1), dim3(1024), 0, stream, H, d, damp, dead, scal, info);
   BPDQ_LAUNCH_CHECK();
@@ -734,8 +1006,14 @@ extern "C" int bpdq_prepare(const float* H, int d_in, float damp, float* U, unsi
       p = first_blk - 1;
     }
     if (ob0 > 0) {
-      hipLaunchKernelGGL(syrk_trailing_kernel, dim3(ob0 * (ob0 + 1) / 2), dim3(256), 0, stream, A, d,
-                         ob0 * NB, (ob1 - ob0) * NB, 0, ob0);
+      const int depth = (ob1 - ob0) * NB;
+      if (ob0 >= kTrail128MinBlocks && d % 2 == 0 && depth % 32 == 0 && ob0 * NB + depth <= d) {
+        hipLaunchKernelGGL(syrk_trailing128_kernel, dim3(trail128_grid(0, ob0)), dim3(256),
+                           kGemmLdsBytes, stream, A, d, ob0 * NB, (ob1 - ob0) * NB, 0, ob0);
+      } else {
+        hipLaunchKernelGGL(syrk_trailing_kernel, dim3(ob0 * (ob0 + 1) / 2), dim3(256), 0, stream, A, d,
+                           ob0 * NB, (ob1 - ob0) * NB, 0, ob0);
+      }
       BPDQ_LAUNCH_CHECK();
     }
   }
@@ -748,6 +1026,16 @@ extern "C" int bpdq_prepare(const float* H, int d_in, float damp, float* U, unsi
     int span = P;
     for (int l = 0; l < dd; ++l) span = (span + 1) / 2;
     const int half = (span + 1) / 2;
+    if (d % NB == 0 && half >= kInverse128MinBlocks) {
+      dim3 grid((half + 1) / 2, (half + 1) / 2, 1 << dd);
+      hipLaunchKernelGGL(tri_inverse_level128_kernel<1>, grid, dim3(256), kGemmLdsBytes, stream, A, d, tmp,
+                         L.ldt, P, dd);
+      BPDQ_LAUNCH_CHECK();
+      hipLaunchKernelGGL(tri_inverse_level128_kernel<2>, grid, dim3(256), kGemmLdsBytes, stream, A, d, tmp,
+                         L.ldt, P, dd);
+      BPDQ_LAUNCH_CHECK();
+      continue;
+    }
     dim3 grid(half, half, 1 << dd);
     hipLaunchKernelGGL(tri_inverse_level_kernel<1>, grid, dim3(256), 0, stream, A, d, tmp, L.ldt, P, dd);
     BPDQ_LAUNCH_CHECK();
