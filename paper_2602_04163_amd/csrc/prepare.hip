@@ -761,7 +761,7 @@ static int trail128_grid(int cb0, int cb1) {
   return 8 * slots;
 }
 // Below this many column blocks the 64-tile kernel has more work-groups to spread over the chip.
-constexpr int kTrail128MinBlocks = 32;
+constexpr int kTrail128MinBlocks = 64;
 // ... and below this many blocks per half of a node, for the products of the inversion
 constexpr int kInverse128MinBlocks = 8;
 
@@ -933,6 +933,26 @@ static PrepLayout prep_layout(int d) {
   return L;
 }
 
+#define BPDQ_TRY(expr)              \
+  do {                              \
+    const int rc_ = (expr);         \
+    if (rc_ != 0) return rc_;       \
+  } while (0)
+
+// The trailing update of column blocks [cb0, cb1) by the factored columns [k0, k0 + depth).
+static int launch_trailing(hipStream_t st, double* A, int d, int k0, int depth, int cb0, int cb1) {
+  if (cb1 <= cb0) return 0;
+  if (cb1 >= kTrail128MinBlocks && d % 2 == 0 && depth % 32 == 0 && k0 + depth <= d) {
+    hipLaunchKernelGGL(syrk_trailing128_kernel, dim3(trail128_grid(cb0, cb1)), dim3(256), kGemmLdsBytes, st,
+                       A, d, k0, depth, cb0, cb1);
+  } else {
+    const int tiles = (cb1 * (cb1 + 1) - cb0 * (cb0 + 1)) / 2;
+    hipLaunchKernelGGL(syrk_trailing_kernel, dim3(tiles), dim3(256), 0, st, A, d, k0, depth, cb0, cb1);
+  }
+  BPDQ_LAUNCH_CHECK();
+  return 0;
+}
+
 }  // namespace bpdq
 
 using namespace bpdq;
@@ -1007,14 +1027,7 @@ extern "C" int bpdq_prepare(const float* H, int d_in, float damp, float* U, unsi
     }
     if (ob0 > 0) {
       const int depth = (ob1 - ob0) * NB;
-      if (ob0 >= kTrail128MinBlocks && d % 2 == 0 && depth % 32 == 0 && ob0 * NB + depth <= d) {
-        hipLaunchKernelGGL(syrk_trailing128_kernel, dim3(trail128_grid(0, ob0)), dim3(256),
-                           kGemmLdsBytes, stream, A, d, ob0 * NB, (ob1 - ob0) * NB, 0, ob0);
-      } else {
-        hipLaunchKernelGGL(syrk_trailing_kernel, dim3(ob0 * (ob0 + 1) / 2), dim3(256), 0, stream, A, d,
-                           ob0 * NB, (ob1 - ob0) * NB, 0, ob0);
-      }
-      BPDQ_LAUNCH_CHECK();
+      BPDQ_TRY(launch_trailing(stream, A, d, ob0 * NB, depth, 0, ob0));
     }
   }
 
