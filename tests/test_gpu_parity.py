@@ -802,3 +802,32 @@ def test_prepare_many_panels_defining_property(dev):
     R = U.double().T @ (U.double() @ Ht[:, idx])
     R[idx, torch.arange(len(idx), device=dev)] -= 1.0
     assert float(R.abs().max()) < 1e-5
+
+
+@pytest.mark.parametrize("d", [4672, 5184, 1088])
+def test_prepare_wide_tile_paths_defining_property(dev, d):
+    """Widths that take the 128 x 128 tile kernels of the factorisation (from 4096 columns on) and
+    of the inversion (from 1024 on) with an odd number of 64-column blocks at several levels of
+    the inversion tree (73, 81 and 17 blocks), so that half-empty tiles occur: the whole of
+    U^T U (H + lambda I) - I in fp64 by torch, and U upper triangular."""
+    print(f"prepare d_in={d} (wide-tile paths, property check)", flush=True)
+    g = torch.Generator(device=dev)
+    g.manual_seed(17 + d)
+    X = torch.randn((2 * d, d), device=dev, generator=g)
+    X *= torch.logspace(-1.0, 1.0, d, device=dev)[None, :]       # channel scales over two decades
+    H = torch.zeros((d, d), device=dev)
+    bq.bpdq_hessian_accumulate(X, H, symmetrize=True)
+    U, dead, info = bq.bpdq_prepare(H, 0.01)
+    torch.cuda.synchronize()
+    assert int(info.item()) == 0
+    assert int(dead.sum().item()) == 0
+    assert float(torch.tril(U, diagonal=-1).abs().max()) == 0.0
+    Ht = H.double()
+    Ht.diagonal().add_(0.01 * float(H.diagonal().mean()))
+    Ud = U.double()
+    R = Ud.T @ (Ud @ Ht)
+    R.diagonal().sub_(1.0)
+    # U is stored in fp32: the residual is its rounding (6e-8 relative) times the condition of the product
+    scale = torch.sqrt(Ht.diagonal())
+    assert float((R / scale[:, None] * scale[None, :]).abs().max()) < 2e-4
+    assert float(R.abs().max()) < 2e-3
