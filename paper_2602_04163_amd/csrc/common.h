@@ -31,7 +31,7 @@ static inline hipError_t bpdq_lds_limit(size_t bytes) {
 }
 
 static inline size_t bpdq_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
-static inline int bpdq_ceil_div(int a, int b) { return (a + b - 1) / b; }
+__host__ __device__ static inline int bpdq_ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 // bump allocator over the caller's workspace
 struct BpdqArena {

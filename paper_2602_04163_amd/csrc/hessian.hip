@@ -142,6 +142,47 @@ __device__ __forceinline__ int xcd_item(int w, int n_off_items, const HessPlan& 
   return base + ((q / tiles) * kNumXCD + y) * tiles + q % tiles;
 }
 
+// Tile order of a launch without token slices (wide layers: more tiles than the chip runs at
+// once).  In row-major order the 32 work-groups an XCD runs at one time meet ~36 different
+// 256-channel panels, each streamed whole through that XCD's L2.  Here the upper triangle is cut
+// into super-blocks of 4 x 8 tiles, their valid tiles (on or above the diagonal) numbered
+// super-block after super-block, and XCD x takes runs 32 of that sequence: x, x + 8, ...  The tiles
+// in flight on an XCD then share 12 panels.  Work-group w -> position in the sequence (or -1
+// beyond the last tile), and from there the tile.
+constexpr int kSuperRows = 4, kSuperCols = 8;
+__host__ __device__ inline int direct_grid(int nb) {
+  const int tiles = nb * (nb + 1) / 2;
+  return bpdq_ceil_div(tiles, kNumCU) * kNumCU;
+}
+__device__ __forceinline__ bool direct_tile(int w, int nb, int& bi, int& bj) {
+  const int per = kNumCU / kNumXCD;                       // 32
+  const int x = w % kNumXCD, n = w / kNumXCD;
+  int seq = ((n / per) * kNumXCD + x) * per + n % per;
+  if (seq >= nb * (nb + 1) / 2) return false;
+  const int row_groups = bpdq_ceil_div(nb, kSuperRows), col_groups = bpdq_ceil_div(nb, kSuperCols);
+  int I = 0;
+  for (; I < row_groups; ++I) {                           // valid tiles of row group I: every bj >= bi
+    int cnt = 0;
+    for (int r = kSuperRows * I; r < kSuperRows * I + kSuperRows && r < nb; ++r) cnt += nb - r;
+    if (seq < cnt) break;
+    seq -= cnt;
+  }
+  for (int J = (kSuperRows * I) / kSuperCols; J < col_groups; ++J) {
+    const int c_lo = kSuperCols * J, c_hi = (c_lo + kSuperCols < nb) ? c_lo + kSuperCols : nb;
+    for (int r = kSuperRows * I; r < kSuperRows * I + kSuperRows && r < nb; ++r) {
+      const int lo = r > c_lo ? r : c_lo;
+      const int cnt = c_hi > lo ? c_hi - lo : 0;
+      if (seq < cnt) {
+        bi = r;
+        bj = lo + seq;
+        return true;
+      }
+      seq -= cnt;
+    }
+  }
+  return false;                                           // not reached: the counts add up to the triangle
+}
+
 // SPLIT false: fp32 matrix cores (v_mfma_f32_32x32x2_f32); true: three bf16 pieces per value and
 // six bf16 products per fp32 product (v_mfma_f32_32x32x16_bf16), same accumulator layout.
 template <bool SPLIT>
@@ -321,17 +362,23 @@ __global__ __launch_bounds__(SplitF16::kThreads, 1) void hess_syrk_f16x2_kernel(
     const uint4* __restrict__ planes, long n_kg, int d_pad, const float* __restrict__ inv, int n_tok,
     int d, float scale, float* __restrict__ H, float* __restrict__ partial, HessPlan p) {
   const int n_off_items = p.n_off * p.S_off;
-  const int item = xcd_item(blockIdx.x, n_off_items, p);
-  int bi, bj, k_begin, k_end;
-  if (item < n_off_items) {
-    decode_off_tile(item % p.n_off, p.nb, bi, bj);
-    k_begin = (item / p.n_off) * p.k_off;
-    k_end = min(n_tok, k_begin + p.k_off);
+  int item = 0, bi, bj, k_begin, k_end;
+  if (p.direct) {
+    if (!direct_tile(blockIdx.x, p.nb, bi, bj)) return;
+    k_begin = 0;
+    k_end = n_tok;
   } else {
-    const int j = item - n_off_items;
-    bi = bj = j % p.n_diag;
-    k_begin = (j / p.n_diag) * p.k_diag;
-    k_end = min(n_tok, k_begin + p.k_diag);
+    item = xcd_item(blockIdx.x, n_off_items, p);
+    if (item < n_off_items) {
+      decode_off_tile(item % p.n_off, p.nb, bi, bj);
+      k_begin = (item / p.n_off) * p.k_off;
+      k_end = min(n_tok, k_begin + p.k_off);
+    } else {
+      const int j = item - n_off_items;
+      bi = bj = j % p.n_diag;
+      k_begin = (j / p.n_diag) * p.k_diag;
+      k_end = min(n_tok, k_begin + p.k_diag);
+    }
   }
   // two stages of 16 tokens per loop iteration; the planes are zero beyond n_tok
   const int n_stage = k_end > k_begin ? 2 * ((k_end - k_begin + 2 * SplitF16::kStageK - 1) / (2 * SplitF16::kStageK)) : 0;
@@ -519,7 +566,8 @@ static int hessian_accumulate(int kind, const float* Xc, int n_tok, int d_in, in
                          dim3(256), 0, stream, Xpart, n_part, d_in, (long)ldx, mul, planes, L.n_kg, L.d_pad);
       BPDQ_LAUNCH_CHECK();
       if (mark_begin()) return BPDQ_ERR_LAUNCH;
-      hipLaunchKernelGGL(hess_syrk_f16x2_kernel, dim3(p.items()), dim3(SplitF16::kThreads),
+      hipLaunchKernelGGL(hess_syrk_f16x2_kernel, dim3(p.direct ? direct_grid(p.nb) : p.items()),
+                         dim3(SplitF16::kThreads),
                          SplitF16::kLdsBytes, stream, planes, L.n_kg, L.d_pad, inv, n_part, d_in, scale,
                          H, partial, p);
     }
