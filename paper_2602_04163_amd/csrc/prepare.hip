@@ -762,8 +762,8 @@ static int trail128_grid(int cb0, int cb1) {
 }
 // Below this many column blocks the 64-tile kernel has more work-groups to spread over the chip.
 constexpr int kTrail128MinBlocks = 64;
-// ... and below this many blocks per half of a node, for the products of the inversion
-constexpr int kInverse128MinBlocks = 8;
+// ... and a level of the inversion tree with fewer 128-tiles than this (two per compute unit)
+constexpr long kInverse128MinTiles = 512;
 
 // ---------------------------------------------------------------- invert -------------------
 // Node `node` of tree depth `depth` over the block range [0, P): ranges are halved
@@ -1039,7 +1039,8 @@ extern "C" int bpdq_prepare(const float* H, int d_in, float damp, float* U, unsi
     int span = P;
     for (int l = 0; l < dd; ++l) span = (span + 1) / 2;
     const int half = (span + 1) / 2;
-    if (d % NB == 0 && half >= kInverse128MinBlocks) {
+    const long tiles128 = ((long)((half + 1) / 2) * ((half + 1) / 2)) << dd;
+    if (d % NB == 0 && tiles128 >= kInverse128MinTiles) {
       dim3 grid((half + 1) / 2, (half + 1) / 2, 1 << dd);
       hipLaunchKernelGGL(tri_inverse_level128_kernel<1>, grid, dim3(256), kGemmLdsBytes, stream, A, d, tmp,
                          L.ldt, P, dd);

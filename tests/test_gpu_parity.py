@@ -804,11 +804,12 @@ def test_prepare_many_panels_defining_property(dev):
     assert float(R.abs().max()) < 1e-5
 
 
-@pytest.mark.parametrize("d", [4672, 5184, 1088])
+@pytest.mark.parametrize("d", [4672, 8256, 1088])
 def test_prepare_wide_tile_paths_defining_property(dev, d):
-    """Widths that take the 128 x 128 tile kernels of the factorisation (from 4096 columns on) and
-    of the inversion (from 1024 on) with an odd number of 64-column blocks at several levels of
-    the inversion tree (73, 81 and 17 blocks), so that half-empty tiles occur: the whole of
+    """Widths around the switches to the 128 x 128 tile kernels: the factorisation takes them from
+    4096 columns on, the inversion for tree levels with at least 512 such tiles.  73 and 129 blocks
+    of 64 columns are odd at several levels of the inversion tree, so half-empty tiles occur
+    (8256 has them in both kernels); 17 blocks stay on the 64-tile kernels.  Checked: the whole of
     U^T U (H + lambda I) - I in fp64 by torch, and U upper triangular."""
     print(f"prepare d_in={d} (wide-tile paths, property check)", flush=True)
     g = torch.Generator(device=dev)
