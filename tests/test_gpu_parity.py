@@ -804,12 +804,14 @@ def test_prepare_many_panels_defining_property(dev):
     assert float(R.abs().max()) < 1e-5
 
 
-@pytest.mark.parametrize("d", [4672, 8256, 1088])
+@pytest.mark.parametrize("d", [4672, 8256, 1088, 4700])
 def test_prepare_wide_tile_paths_defining_property(dev, d):
     """Widths around the switches to the 128 x 128 tile kernels: the factorisation takes them from
     4096 columns on, the inversion for tree levels with at least 512 such tiles.  73 and 129 blocks
     of 64 columns are odd at several levels of the inversion tree, so half-empty tiles occur
-    (8256 has them in both kernels); 17 blocks stay on the 64-tile kernels.  Checked: the whole of
+    (8256 has them in both kernels); 17 blocks stay on the 64-tile kernels; 4700 is ragged (its last
+    block has 28 columns), so the rightmost outer block is updated by the 64-tile kernel and the
+    others by the 128-tile one.  Checked: the whole of
     U^T U (H + lambda I) - I in fp64 by torch, and U upper triangular."""
     print(f"prepare d_in={d} (wide-tile paths, property check)", flush=True)
     g = torch.Generator(device=dev)
