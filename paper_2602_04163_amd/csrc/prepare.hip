@@ -8,13 +8,15 @@
 // workspace; the result is rounded to fp32 once, on output.
 //
 //   factor : right-looking over 64-column panels from the right, two panels per launch: every
-//            panel work-group factors the diagonal blocks in registers and solves its 64 rows
-//            of R12 R22^T = A12.  The
-//            trailing update A11 -= R12 R12^T (fp64 MFMA, upper 64 x 64 tiles) is two-level:
-//            after each panel only inside the current 512-column outer panel, and once per
-//            outer panel, with K = 512, on everything to its left.
+//            panel work-group factors the two diagonal blocks for itself (in LDS, by panels of
+//            16 columns) and solves its 64 rows of R12 R22^T = A12.  The trailing update
+//            A11 -= R12 R12^T (fp64 MFMA) is two-level: after each panel pair only inside the
+//            current 512-column outer block (64 x 64 tiles), and once per outer block, with
+//            K = 512, on everything to its left (128 x 128 tiles fed by LDS-DMA from 4096
+//            columns on).
 //   invert : divide and conquer over block ranges, [R11 R12; 0 R22]^-1 =
-//            [U11, -U11 R12 U22; 0, U22]; every tree level is two launches.
+//            [U11, -U11 R12 U22; 0, U22]; every tree level is two launches (128 x 128 tiles
+//            where a level has enough of them, 64 x 64 otherwise).
 #include "common.h"
 
 namespace bpdq {
