@@ -861,7 +861,12 @@ __global__ __launch_bounds__(256, 2) void tri_inverse_level128_kernel(double* __
   int lo, mid, hi;
   if (!tree_node(P, depth, blockIdx.z, lo, mid, hi)) return;
   const int n_rows = (mid - lo) * NB, n_cols = (hi - mid) * NB;
-  const int r_loc = blockIdx.y * kGemmTile, c_loc = blockIdx.x * kGemmTile;   // inside the node
+  // Work-groups go to the 8 XCDs in turn (x fastest).  The tile column is rotated by the tile row:
+  // otherwise, whenever the tile count per row is a multiple of 8, one XCD would get all the
+  // longest (or shortest) K ranges, which grow with the column (MODE 1) or shrink with the row.
+  // (Super-blocks of 4 x 4 tiles per XCD, for L2 reuse, were measured and were slower.)
+  const int r_loc = blockIdx.y * kGemmTile;
+  const int c_loc = (int)((blockIdx.x + blockIdx.y) % gridDim.x) * kGemmTile;   // inside the node
   if (r_loc >= n_rows || c_loc >= n_cols) return;
   const int row0 = lo * NB + r_loc, row_limit = mid * NB;     // global rows of the tile
   const int col0 = mid * NB + c_loc, col_limit = hi * NB;     // global columns of the tile (in A)
