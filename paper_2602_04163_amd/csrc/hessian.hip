@@ -109,14 +109,34 @@ static HessPlan plan_hessian(int n_tok, int d_in, int kind) {
   return p;
 }
 
-// off-diagonal tile index (row-major over bi < bj) -> (bi, bj)
+// Off-diagonal tile index -> (bi, bj), bi < bj.  The strict upper triangle is walked super-block
+// after super-block (8 rows x 4 columns of tiles, row-major inside): the 32 tiles of a slice that
+// an XCD has in flight then share about 12 of the 256-channel panels; in plain row-major order a
+// run of 32 tiles is one row of a wide layer and meets 33.
+constexpr int kSuperRows = 8, kSuperCols = 4;
 __device__ __forceinline__ void decode_off_tile(int tile, int nb, int& bi, int& bj) {
-  bi = 0;
-  while (tile >= nb - 1 - bi) {
-    tile -= nb - 1 - bi;
-    ++bi;
+  const int row_groups = bpdq_ceil_div(nb, kSuperRows), col_groups = bpdq_ceil_div(nb, kSuperCols);
+  int I = 0;
+  for (; I < row_groups - 1; ++I) {                       // tiles of row group I: every bj > bi
+    int cnt = 0;
+    for (int r = kSuperRows * I; r < kSuperRows * I + kSuperRows && r < nb; ++r) cnt += nb - 1 - r;
+    if (tile < cnt) break;
+    tile -= cnt;
   }
-  bj = bi + 1 + tile;
+  bi = bj = 0;
+  for (int J = (kSuperRows * I + 1) / kSuperCols; J < col_groups; ++J) {
+    const int c_lo = kSuperCols * J, c_hi = (c_lo + kSuperCols < nb) ? c_lo + kSuperCols : nb;
+    for (int r = kSuperRows * I; r < kSuperRows * I + kSuperRows && r < nb; ++r) {
+      const int lo = r + 1 > c_lo ? r + 1 : c_lo;
+      const int cnt = c_hi > lo ? c_hi - lo : 0;
+      if (tile < cnt) {
+        bi = r;
+        bj = lo + tile;
+        return;
+      }
+      tile -= cnt;
+    }
+  }
 }
 
 // Work-group -> work item.  Work-groups are handed to the 8 XCDs round-robin (work-group w runs
@@ -145,12 +165,11 @@ __device__ __forceinline__ int xcd_item(int w, int n_off_items, const HessPlan& 
 // Tile order of a launch without token slices (wide layers: more tiles than the chip runs at
 // once).  In row-major order the 32 work-groups an XCD runs at one time meet ~36 different
 // 256-channel panels, each streamed whole through that XCD's L2.  Here the upper triangle is cut
-// into super-blocks of 8 x 4 tiles, their valid tiles (on or above the diagonal) numbered
+// into the same super-blocks of 8 x 4 tiles, their valid tiles (on or above the diagonal) numbered
 // super-block after super-block, and XCD x takes the runs of 32 numbered x, x + 8, ... of that
 // sequence.  The tiles in flight on an XCD then share 12 to 17 panels (8 x 4 measured 2.5 % faster
 // than 4 x 8 or 2 x 16).  Work-group w -> position in the sequence (none beyond the last tile),
 // and from there the tile.
-constexpr int kSuperRows = 8, kSuperCols = 4;
 __host__ __device__ inline int direct_grid(int nb) {
   const int tiles = nb * (nb + 1) / 2;
   return bpdq_ceil_div(tiles, kNumCU) * kNumCU;
