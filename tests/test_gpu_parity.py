@@ -146,7 +146,24 @@ def test_hessian_host_split_launches(dev, kernel):
     Hg = H[idx][:, idx].cpu().numpy().astype(np.float64)
     assert _relfro(Hg, Hsub) < H_TOL
     assert torch.equal(H, H.T)
-    del X, H
+    # every 256 x 256 tile of the result (the launch walks the triangle in an order of its own: a
+    # tile left out or taken twice would pass a sampled check with some probability), against
+    # the definition evaluated in fp64 by torch on 4096 of the tokens
+    H.zero_()
+    accumulate(X[:4096], H, symmetrize=True)
+    Xd = X[:4096].double()
+    Hd = 2.0 * (Xd.T @ Xd)
+    del Xd
+    err = (H.double() - Hd).square_()
+    nt = d_in // 256
+    tile_err = err.view(nt, 256, nt, 256).sum(dim=(1, 3))
+    tile_ref = Hd.square_().view(nt, 256, nt, 256).sum(dim=(1, 3))
+    # an off-diagonal tile of uncorrelated channels is pure noise (entries ~ sqrt(N)), so its own
+    # rounding error is set against the size of the diagonal entries that bound it
+    scale = torch.sqrt(tile_ref.diagonal()[:, None] * tile_ref.diagonal()[None, :])
+    assert float((tile_err / scale).max()) < H_TOL ** 2
+    assert float(torch.sqrt(tile_err.sum() / tile_ref.sum())) < H_TOL
+    del X, H, Hd, err
     n_tok = 530000 if kernel != "f32" else 1060000
     print(f"hessian {kernel} {n_tok} tokens", flush=True)
     d_in = 8
