@@ -109,34 +109,51 @@ static HessPlan plan_hessian(int n_tok, int d_in, int kind) {
   return p;
 }
 
-// Off-diagonal tile index -> (bi, bj), bi < bj.  The strict upper triangle is walked super-block
-// after super-block (8 rows x 4 columns of tiles, row-major inside): the 32 tiles of a slice that
-// an XCD has in flight then share about 12 of the 256-channel panels; in plain row-major order a
-// run of 32 tiles is one row of a wide layer and meets 33.
-constexpr int kSuperRows = 8, kSuperCols = 4;
-__device__ __forceinline__ void decode_off_tile(int tile, int nb, int& bi, int& bj) {
-  const int row_groups = bpdq_ceil_div(nb, kSuperRows), col_groups = bpdq_ceil_div(nb, kSuperCols);
-  int I = 0;
-  for (; I < row_groups - 1; ++I) {                       // tiles of row group I: every bj > bi
-    int cnt = 0;
-    for (int r = kSuperRows * I; r < kSuperRows * I + kSuperRows && r < nb; ++r) cnt += nb - 1 - r;
-    if (tile < cnt) break;
-    tile -= cnt;
-  }
+// Tile orders.  The 32 tiles an XCD has in flight stream their 256-channel panels through its L2,
+// so an order is as good as the number of different panels a run of 32 consecutive tiles meets.
+// The triangle is cut into blocks of kTileBlock panels: the blocks on the diagonal are cliques
+// (every pair of kTileBlock panels: 28 tiles on 8 panels), the others kTileBlock x kTileBlock
+// squares (64 tiles on 16 panels); blocks are taken column by column, tiles row-major inside.
+// On 74 x 74 tiles a run of 32 meets 13 panels on average, in plain row-major order 32.  Measured
+// against row-major in one process: 6.5 % less time at 116 x 116 tiles, 2-3 % at 74 and 32, none at 14.
+constexpr int kTileBlock = 8;
+
+// seq-th tile of that order -> (bi, bj).  DIAG: the diagonal tiles are part of the sequence
+// (bi <= bj), else only bi < bj.  seq must be below the number of such tiles.
+template <bool DIAG>
+__device__ __forceinline__ void block_order_tile(int seq, int nb, int& bi, int& bj) {
+  const int n_blk = bpdq_ceil_div(nb, kTileBlock);
   bi = bj = 0;
-  for (int J = (kSuperRows * I + 1) / kSuperCols; J < col_groups; ++J) {
-    const int c_lo = kSuperCols * J, c_hi = (c_lo + kSuperCols < nb) ? c_lo + kSuperCols : nb;
-    for (int r = kSuperRows * I; r < kSuperRows * I + kSuperRows && r < nb; ++r) {
-      const int lo = r + 1 > c_lo ? r + 1 : c_lo;
-      const int cnt = c_hi > lo ? c_hi - lo : 0;
-      if (tile < cnt) {
-        bi = r;
-        bj = lo + tile;
-        return;
-      }
-      tile -= cnt;
+  for (int bc = 0; bc < n_blk; ++bc) {
+    const int c0 = bc * kTileBlock, mc = (c0 + kTileBlock < nb ? kTileBlock : nb - c0);
+    // the column of blocks above the diagonal one: bc full squares of kTileBlock x mc tiles
+    const int above = bc * kTileBlock * mc;
+    if (seq < above) {
+      const int br = seq / (kTileBlock * mc), t = seq % (kTileBlock * mc);
+      bi = br * kTileBlock + t / mc;
+      bj = c0 + t % mc;
+      return;
     }
+    seq -= above;
+    const int clique = DIAG ? mc * (mc + 1) / 2 : mc * (mc - 1) / 2;
+    if (seq < clique) {
+      for (int r = 0; r < mc; ++r) {
+        const int cnt = DIAG ? mc - r : mc - 1 - r;
+        if (seq < cnt) {
+          bi = c0 + r;
+          bj = c0 + r + (DIAG ? 0 : 1) + seq;
+          return;
+        }
+        seq -= cnt;
+      }
+    }
+    seq -= clique;
   }
+}
+
+// off-diagonal tile index -> (bi, bj), bi < bj
+__device__ __forceinline__ void decode_off_tile(int tile, int nb, int& bi, int& bj) {
+  block_order_tile<false>(tile, nb, bi, bj);
 }
 
 // Work-group -> work item.  Work-groups are handed to the 8 XCDs round-robin (work-group w runs
@@ -163,13 +180,9 @@ __device__ __forceinline__ int xcd_item(int w, int n_off_items, const HessPlan& 
 }
 
 // Tile order of a launch without token slices (wide layers: more tiles than the chip runs at
-// once).  In row-major order the 32 work-groups an XCD runs at one time meet ~36 different
-// 256-channel panels, each streamed whole through that XCD's L2.  Here the upper triangle is cut
-// into the same super-blocks of 8 x 4 tiles, their valid tiles (on or above the diagonal) numbered
-// super-block after super-block, and XCD x takes the runs of 32 numbered x, x + 8, ... of that
-// sequence.  The tiles in flight on an XCD then share 12 to 17 panels (8 x 4 measured 2.5 % faster
-// than 4 x 8 or 2 x 16).  Work-group w -> position in the sequence (none beyond the last tile),
-// and from there the tile.
+// once): the block order above over the whole upper triangle, diagonal tiles included, and XCD x
+// takes the runs of 32 numbered x, x + 8, ... of that sequence (work-group w runs on XCD w % 8).
+// Work-group w -> tile; false beyond the last tile.
 __host__ __device__ inline int direct_grid(int nb) {
   const int tiles = nb * (nb + 1) / 2;
   return bpdq_ceil_div(tiles, kNumCU) * kNumCU;
@@ -177,30 +190,10 @@ __host__ __device__ inline int direct_grid(int nb) {
 __device__ __forceinline__ bool direct_tile(int w, int nb, int& bi, int& bj) {
   const int per = kNumCU / kNumXCD;                       // 32
   const int x = w % kNumXCD, n = w / kNumXCD;
-  int seq = ((n / per) * kNumXCD + x) * per + n % per;
+  const int seq = ((n / per) * kNumXCD + x) * per + n % per;
   if (seq >= nb * (nb + 1) / 2) return false;
-  const int row_groups = bpdq_ceil_div(nb, kSuperRows), col_groups = bpdq_ceil_div(nb, kSuperCols);
-  int I = 0;
-  for (; I < row_groups; ++I) {                           // valid tiles of row group I: every bj >= bi
-    int cnt = 0;
-    for (int r = kSuperRows * I; r < kSuperRows * I + kSuperRows && r < nb; ++r) cnt += nb - r;
-    if (seq < cnt) break;
-    seq -= cnt;
-  }
-  for (int J = (kSuperRows * I) / kSuperCols; J < col_groups; ++J) {
-    const int c_lo = kSuperCols * J, c_hi = (c_lo + kSuperCols < nb) ? c_lo + kSuperCols : nb;
-    for (int r = kSuperRows * I; r < kSuperRows * I + kSuperRows && r < nb; ++r) {
-      const int lo = r > c_lo ? r : c_lo;
-      const int cnt = c_hi > lo ? c_hi - lo : 0;
-      if (seq < cnt) {
-        bi = r;
-        bj = lo + seq;
-        return true;
-      }
-      seq -= cnt;
-    }
-  }
-  return false;                                           // not reached: the counts add up to the triangle
+  block_order_tile<true>(seq, nb, bi, bj);
+  return true;
 }
 
 // SPLIT false: fp32 matrix cores (v_mfma_f32_32x32x2_f32); true: three bf16 pieces per value and
