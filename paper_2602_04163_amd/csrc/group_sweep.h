@@ -608,6 +608,9 @@ __global__ __launch_bounds__(kSweepThreads, kSweepWavesPerSimd<G>) void bpdq_gro
       return;
     }
   }
+  // the sweep is the critical path of the launch: where a sweeping and an updating wavefront share
+  // a SIMD, the sweeping one issues first
+  __builtin_amdgcn_s_setprio(3);
   constexpr int CPL = G / 16;
   extern __shared__ float lds[];
   float* sU = lds;                            // packed local factor, see SuLayout
@@ -690,6 +693,9 @@ __global__ __launch_bounds__(kSweepThreads, kSweepWavesPerSimd<G>) void uniform_
       return;
     }
   }
+  // the sweep is the critical path of the launch: where a sweeping and an updating wavefront share
+  // a SIMD, the sweeping one issues first
+  __builtin_amdgcn_s_setprio(3);
   constexpr int CPL = G / 16;
   extern __shared__ float lds[];
   float* sU = lds;
