@@ -183,61 +183,102 @@ __device__ __forceinline__ void factor64_blocked(double (*sD)[NB + 1], double* s
 }
 
 
-// X R^T = A for one or two 64 x 64 tiles at once, in place, by blocks of 16 columns from the
-// right (R upper, sInvD[j] = 1 / R_jj):
-//   (1) inside a block: substitution, one lane per row (wavefront 0 takes sXa, wavefront 1 sXb);
-//   (2) the blocks to its left receive  A_J' -= X_J R[J', J]^T  on the fp64 matrix cores
-//       (v_mfma_f64_16x16x4_f64; wavefront w takes rows 16 w .. 16 w + 15 of both tiles).
-// A quarter of the dependent multiply-adds of a plain substitution stay on the critical path.
+// Inverses of the four 16 x 16 diagonal blocks of R (upper triangular, sInvD[j] = 1 / R_jj):
+// sRinv[J][i][c] = (R_JJ^-1)[i][c], zero below the diagonal.  Wavefront J takes block J, lane
+// c < 16 column c by back substitution from row 15 up (rows below c are zero, row c is 1 / R_cc).
 // All 256 threads call this; it ends with a barrier.
-__device__ __forceinline__ void trsm_block_subst(double (*sX)[NB + 1], int row, int J,
-                                                 const double (*sR)[NB + 1], const double* sInvD) {
-  double x[16];
+typedef double Inv16[16][16];
+__device__ __forceinline__ void invert_diag16(const double (*sR)[NB + 1], const double* sInvD, Inv16* sRinv) {
+  const int lane = threadIdx.x & 63, J = threadIdx.x >> 6;
+  if (lane < 16) {
+    const int c = lane, o = 16 * J;
+    double x[16];
 #pragma unroll
-  for (int c = 0; c < 16; ++c) x[c] = sX[row][16 * J + c];
+    for (int i = 15; i >= 0; --i) {
+      double acc = 0.0;
 #pragma unroll
-  for (int c = 15; c >= 0; --c) {
-    x[c] *= sInvD[16 * J + c];
-#pragma unroll
-    for (int k = 0; k < c; ++k) x[k] = fma(-x[c], sR[16 * J + k][16 * J + c], x[k]);
-  }
-#pragma unroll
-  for (int c = 0; c < 16; ++c) sX[row][16 * J + c] = x[c];
-}
-
-__device__ __forceinline__ void trsm_block_update(double (*sX)[NB + 1], int J,
-                                                  const double (*sR)[NB + 1]) {
-  const int lane = threadIdx.x & 63, i0 = 16 * (threadIdx.x >> 6);
-  const int lm = lane & 15, lq = lane >> 4;
-  double a[4];
-#pragma unroll
-  for (int ks = 0; ks < 4; ++ks) a[ks] = sX[i0 + lm][16 * J + 4 * ks + lq];      // A[m][k] = X_J
-  for (int Jp = 0; Jp < J; ++Jp) {
-    f64x4 acc = (f64x4){0.0, 0.0, 0.0, 0.0};
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      const double b = sR[16 * Jp + lm][16 * J + 4 * ks + lq];                    // B[k][n] = R[J'n][Jk]
-      acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a[ks], b, acc, 0, 0, 0);
+      for (int m = 15; m > i; --m) acc = fma(sR[o + i][o + m], x[m], acc);   // (x[m] = 0 for m > c) the newest x last:
+                                                                             // only that term waits for the row before
+      const double v = (i == c) ? 1.0 : -acc;
+      x[i] = (i <= c) ? v * sInvD[o + i] : 0.0;
     }
 #pragma unroll
-    for (int r = 0; r < 4; ++r) sX[i0 + 4 * r + lq][16 * Jp + lm] -= acc[r];       // D[4r + l/16][l%16]
+    for (int i = 0; i < 16; ++i) sRinv[J][i][c] = x[i];
+  }
+  __syncthreads();
+}
+
+// X R^T = A for one or two 64 x 64 tiles at once, in place, by blocks of 16 columns from the
+// right (R upper, sRinv = inverses of its 16 x 16 diagonal blocks), all on the fp64 matrix cores
+// (v_mfma_f64_16x16x4_f64):
+//   (1) X_J = A_J R_JJ^-T;
+//   (2) the blocks to its left receive  A_J' -= X_J R[J', J]^T.
+// Wavefront w takes rows 16 w .. 16 w + 15 of both tiles through all four blocks; a row block
+// never meets another one's data, so there is no barrier inside and no dependent substitution
+// chain: against a column-by-column substitution inside each block (one lane per row, 120 LDS
+// broadcasts per block) a solve takes 2 us instead of 7.
+// All 256 threads call this; it ends with a barrier.
+// One block step for TILES tiles at once (their chains of dependent matrix instructions
+// interleave): X_J = A_J R_JJ^-T, then A_J' -= X_J R[J', J]^T for every J' < J.
+template <int J, int TILES>
+__device__ __forceinline__ void trsm_block_step(double (*const (&sX)[2])[NB + 1], const double (*sR)[NB + 1],
+                                                const Inv16* sRinv) {
+  const int lane = threadIdx.x & 63, i0 = 16 * (threadIdx.x >> 6);
+  const int lm = lane & 15, lq = lane >> 4;
+  double a[TILES][4], b[4];
+  f64x4 acc[TILES];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    b[ks] = sRinv[J][lm][4 * ks + lq];                                             // B[k][n] = Rinv[n][k]
+#pragma unroll
+    for (int t = 0; t < TILES; ++t) a[t][ks] = sX[t][i0 + lm][16 * J + 4 * ks + lq];   // A[m][k] = A_J
+  }
+#pragma unroll
+  for (int t = 0; t < TILES; ++t) acc[t] = (f64x4){0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+    for (int t = 0; t < TILES; ++t) acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[t][ks], b[ks], acc[t], 0, 0, 0);
+#pragma unroll
+  for (int t = 0; t < TILES; ++t)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) sX[t][i0 + 4 * r + lq][16 * J + lm] = acc[t][r];   // D[4r + l/16][l%16]
+  if constexpr (J > 0) {
+    // X_J back in operand layout (this wavefront's own rows: LDS serves a wavefront in order)
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+      for (int t = 0; t < TILES; ++t) a[t][ks] = sX[t][i0 + lm][16 * J + 4 * ks + lq];
+    f64x4 upd[J][TILES];
+#pragma unroll
+    for (int Jp = 0; Jp < J; ++Jp) {
+      double br[4];
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) br[ks] = sR[16 * Jp + lm][16 * J + 4 * ks + lq];   // B[k][n] = R[J'n][Jk]
+#pragma unroll
+      for (int t = 0; t < TILES; ++t) upd[Jp][t] = (f64x4){0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+        for (int t = 0; t < TILES; ++t)
+          upd[Jp][t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[t][ks], br[ks], upd[Jp][t], 0, 0, 0);
+    }
+#pragma unroll
+    for (int Jp = 0; Jp < J; ++Jp)
+#pragma unroll
+      for (int t = 0; t < TILES; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) sX[t][i0 + 4 * r + lq][16 * Jp + lm] -= upd[Jp][t][r];
+    trsm_block_step<J - 1, TILES>(sX, sR, sRinv);
   }
 }
 
 __device__ __forceinline__ void trsm64_blocked(double (*sXa)[NB + 1], double (*sXb)[NB + 1], bool two,
-                                               const double (*sR)[NB + 1], const double* sInvD) {
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-#pragma unroll 1
-  for (int J = NB / 16 - 1; J >= 0; --J) {
-    if (w == 0) trsm_block_subst(sXa, lane, J, sR, sInvD);
-    else if (w == 1 && two) trsm_block_subst(sXb, lane, J, sR, sInvD);
-    __syncthreads();
-    if (J > 0) {
-      trsm_block_update(sXa, J, sR);
-      if (two) trsm_block_update(sXb, J, sR);
-    }
-    __syncthreads();
-  }
+                                               const double (*sR)[NB + 1], const Inv16* sRinv) {
+  double (*const tiles[2])[NB + 1] = {sXa, sXb};
+  if (two) trsm_block_step<NB / 16 - 1, 2>(tiles, sR, sRinv);
+  else trsm_block_step<NB / 16 - 1, 1>(tiles, sR, sRinv);
+  __syncthreads();
 }
 
 // The symmetric 64 x 64 block at (p0, p0), both triangles (only the upper triangle of A is valid),
@@ -270,6 +311,7 @@ __global__ __launch_bounds__(256) void panel_factor_kernel(double* __restrict__ 
   __shared__ double sA[NB][NB + 1];     // panel tile of this work-group
   __shared__ double col[2][NB];
   __shared__ double sInvD[NB];
+  __shared__ Inv16 sRinv[NB / 16];
   const int tid = threadIdx.x;
 
   {
@@ -293,7 +335,8 @@ __global__ __launch_bounds__(256) void panel_factor_kernel(double* __restrict__ 
     if (tid == 0) *pair_flag = 0;
   }
   if (n_above == 0) return;
-  trsm64_blocked(sA, sA, false, sR, sInvD);
+  invert_diag16(sR, sInvD, sRinv);
+  trsm64_blocked(sA, sA, false, sR, sRinv);
   for (int e = tid; e < NB * NB; e += 256) {
     const int i = e / NB, j = e % NB;
     if (r0 + i < p0 && j < nb) A[(long)(r0 + i) * d + p0 + j] = sA[i][j];
@@ -413,7 +456,7 @@ __device__ __forceinline__ void quad_for_each(const Quad64& q, F f) {
 // launches of the panel chain (each is short and latency-bound).  Work-group 0 writes R11, R22
 // to Rdiag and R12 to R12buf (never into A, whose blocks later-scheduled work-groups still
 // read) and sets the pair flag of b2, so that the inverse step puts R12 in place.
-constexpr size_t kPairLdsBytes = (size_t)(4 * NB * (NB + 1) + 3 * NB) * sizeof(double);
+constexpr size_t kPairLdsBytes = (size_t)(4 * NB * (NB + 1) + 3 * NB + NB * 16) * sizeof(double);
 
 __global__ __launch_bounds__(256) void panel_pair_kernel(double* __restrict__ A, int d, int p1,
                                                          int nb2, int n_above,
@@ -430,6 +473,7 @@ __global__ __launch_bounds__(256) void panel_pair_kernel(double* __restrict__ A,
   Row* sA2 = sA1 + NB;                              // own rows, columns of b2
   double (*col)[NB] = reinterpret_cast<double (*)[NB]>(dyn + 4 * NB * (NB + 1));
   double* sInvD = dyn + 4 * NB * (NB + 1) + 2 * NB;
+  Inv16* sRinv = reinterpret_cast<Inv16*>(dyn + 4 * NB * (NB + 1) + 3 * NB);
   const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
   const int p2 = p1 + NB;
   const int r0 = blockIdx.x * NB;
@@ -457,8 +501,8 @@ __global__ __launch_bounds__(256) void panel_pair_kernel(double* __restrict__ A,
   if (first)
     for (int e = tid; e < NB * NB; e += 256) Rdiag2[e] = sR[e / NB][e % NB];
   // R12 = D12 R22^-T and X2 = A2 R22^-T
-  __syncthreads();                                  // Rdiag2 has been read out of sR
-  trsm64_blocked(sR12, sA2, n_above > 0, sR, sInvD);
+  invert_diag16(sR, sInvD, sRinv);                  // (its barrier: Rdiag2 has been read out of sR)
+  trsm64_blocked(sR12, sA2, n_above > 0, sR, sRinv);
   {
     Quad64 q;
     quad_zero(q);
@@ -488,7 +532,8 @@ __global__ __launch_bounds__(256) void panel_pair_kernel(double* __restrict__ A,
     }
   }
   if (n_above == 0) return;
-  trsm64_blocked(sA1, sA1, false, sR, sInvD);
+  invert_diag16(sR, sInvD, sRinv);
+  trsm64_blocked(sA1, sA1, false, sR, sRinv);
   for (int e = tid; e < NB * NB; e += 256) {
     const int i = e / NB, j = e % NB;
     if (r0 + i < p1) {
